@@ -1,0 +1,257 @@
+// Host side of librr.so: argument validation, workspace layout, stage sequencing, profiling record.
+#include <math.h>
+#include <string.h>
+
+#include <vector>
+
+#include "rr_internal.h"
+
+namespace rr {
+
+// ------------------------------------------------------------------ profiling record
+struct ProfSpan { int id; hipEvent_t a, b; };
+static bool g_prof_on = false;
+static std::vector<ProfSpan> g_spans;       // recorded launches since the last read
+static std::vector<hipEvent_t> g_free_events;
+static hipEvent_t g_open[K_COUNT];
+static const char *const g_kernel_names[K_COUNT] = {
+    "router_scores", "topk_rank", "scan_candidates", "plan_rounds", "scatter_candidates", "select_slot",
+    "ir_count", "ir_scan", "row_plan", "ir_weights", "dispatch_gather", "ffn_gate_up", "ffn_down", "combine"};
+
+static hipEvent_t get_event() {
+  if (!g_free_events.empty()) {
+    hipEvent_t e = g_free_events.back();
+    g_free_events.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+void prof_begin(KernelId id, hipStream_t s) {
+  if (!g_prof_on) return;
+  hipEvent_t e = get_event();
+  g_open[id] = e;
+  if (e) (void)hipEventRecord(e, s);
+}
+
+void prof_end(KernelId id, hipStream_t s) {
+  if (!g_prof_on) return;
+  hipEvent_t a = g_open[id];
+  hipEvent_t b = get_event();
+  if (!a || !b) return;
+  (void)hipEventRecord(b, s);
+  g_spans.push_back({(int)id, a, b});
+}
+
+// ------------------------------------------------------------------ configuration
+static int round_up(int a, int b) { return (a + b - 1) / b * b; }
+
+static int make_dims(const rr_config *c, bool need_ffn, Dims *D) {
+  if (!c) return RR_ERR_INVALID_ARG;
+  if (c->T <= 0 || c->E <= 0 || c->k <= 0 || c->G <= 0 || c->d_model <= 0) return RR_ERR_INVALID_ARG;
+  if (c->E % c->G || c->T % c->G || c->k > c->E) return RR_ERR_INVALID_ARG;
+  if ((c->flags & RR_FILL_IN) && c->k + 1 > c->E) return RR_ERR_INVALID_ARG;
+  if (!(c->capacity_factor > 0.0f) || !isfinite(c->capacity_factor)) return RR_ERR_INVALID_ARG;
+  if (c->flags & ~(uint32_t)(RR_INTRA_GPU | RR_FILL_IN | RR_POLICY_ARRIVAL)) return RR_ERR_INVALID_ARG;
+  if (c->E > kMaxE || c->k > kMaxK || c->T > (1 << 24)) return RR_ERR_UNSUPPORTED;
+  if (c->dtype != RR_F32 && c->dtype != RR_BF16) return RR_ERR_UNSUPPORTED;
+  if (c->d_model % 8) return RR_ERR_UNSUPPORTED;
+  if (need_ffn) {
+    if (c->d_ff <= 0) return RR_ERR_INVALID_ARG;
+    if (c->d_ff % 8) return RR_ERR_UNSUPPORTED;
+    if (c->act != RR_ACT_GELU && c->act != RR_ACT_SWIGLU) return RR_ERR_UNSUPPORTED;
+  }
+  int32_t C = rr_capacity(c->T, c->E, c->capacity_factor);
+  if (C < 1) return RR_ERR_INVALID_ARG;
+  if ((int64_t)C * c->E > ((int64_t)1 << 28)) return RR_ERR_UNSUPPORTED;
+  D->T = c->T; D->d = c->d_model; D->F = c->d_ff > 0 ? c->d_ff : 0; D->E = c->E; D->k = c->k; D->G = c->G; D->C = C;
+  D->Eg = c->E / c->G; D->Tg = c->T / c->G;
+  D->ir = (c->flags & RR_INTRA_GPU) ? 1 : 0;
+  D->fr = (c->flags & RR_FILL_IN) ? 1 : 0;
+  D->arrival = (c->flags & RR_POLICY_ARRIVAL) ? 1 : 0;
+  D->NR = c->k + D->fr;
+  D->NCAT = D->NR * c->E;
+  D->NB = (c->T + kTokBlock - 1) / kTokBlock;
+  D->dtype = c->dtype; D->act = c->act;
+  int64_t slots = (int64_t)C * c->E, assigns = (int64_t)D->NR * c->T;
+  int64_t rmax = (slots < assigns ? slots : assigns) + (D->ir ? c->T : 0);
+  if (rmax > ((int64_t)1 << 28)) return RR_ERR_UNSUPPORTED;
+  D->Rmax = (int)rmax;
+  D->BM = c->dtype == RR_BF16 ? 256 : 64;
+  D->max_mtiles = D->Rmax / D->BM + c->E;
+  return RR_OK;
+}
+
+// Lays the Work arrays out in the workspace; with base == nullptr only measures.
+struct Carver {
+  char *base; size_t off;
+  template <typename Tp> Tp *take(size_t n) {
+    size_t bytes = (n * sizeof(Tp) + 255) / 256 * 256;
+    Tp *p = base ? reinterpret_cast<Tp *>(base + off) : nullptr;
+    off += bytes;
+    return p;
+  }
+};
+
+static size_t carve(const Dims &D, bool forward, void *ws, Work *W) {
+  Carver cv{static_cast<char *>(ws), 0};
+  size_t T = D.T, NR = D.NR, E = D.E;
+  W->key = cv.take<u32>(T * NR);
+  W->ir_score = cv.take<float>(T);
+  W->ir_cand = cv.take<int32_t>(T);
+  W->blk_cnt = cv.take<int32_t>((size_t)D.NCAT * D.NB);
+  W->cat_cnt = cv.take<int32_t>(D.NCAT);
+  W->cat_m = cv.take<int32_t>(D.NCAT);
+  W->cat_fill0 = cv.take<int32_t>(D.NCAT);
+  W->cat_base = cv.take<int32_t>(D.NCAT);
+  W->cand_key = cv.take<u32>(T * NR);
+  W->cand_tok = cv.take<int32_t>(T * NR);
+  W->ir_blk_cnt = cv.take<int32_t>(E * D.NB);
+  W->ir_cnt = cv.take<int32_t>(E);
+  W->row_base = cv.take<int32_t>(E + 1);
+  W->tile_expert = cv.take<int32_t>(D.max_mtiles);
+  W->tile_row0 = cv.take<int32_t>(D.max_mtiles);
+  W->n_tiles = cv.take<int32_t>(1);
+  if (forward) {
+    size_t K1 = D.k + 1, es = D.dtype == RR_BF16 ? 2 : 4;
+    W->logits = cv.take<float>(T * E);
+    W->tables.rank_expert = cv.take<int32_t>(T * K1);
+    W->tables.slot = cv.take<int32_t>(T * K1);
+    W->tables.slot_token = cv.take<int32_t>(E * D.C);
+    W->tables.fill_topk = cv.take<int32_t>(E);
+    W->tables.fill_total = cv.take<int32_t>(E);
+    W->tables.ir_expert = cv.take<int32_t>(T);
+    W->tables.ir_row = cv.take<int32_t>(T);
+    W->tables.ir_offset = cv.take<int32_t>(E + 1);
+    W->tables.ir_token = cv.take<int32_t>(T);
+    W->tables.combine_w = cv.take<float>(T * (D.k + 2));
+    W->x_disp = cv.take<char>((size_t)D.Rmax * D.d * es);
+    W->h = cv.take<char>((size_t)D.Rmax * D.F * es);
+    W->y = cv.take<char>((size_t)D.Rmax * D.d * es);
+  }
+  return cv.off;
+}
+
+static bool tables_complete(const rr_tables *t) {
+  return t && t->rank_expert && t->slot && t->slot_token && t->fill_topk && t->fill_total && t->ir_expert &&
+         t->ir_row && t->ir_offset && t->ir_token && t->combine_w;
+}
+
+static int check_ws(const Dims &D, bool forward, void *ws, size_t ws_bytes, Work *W) {
+  if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255)) return RR_ERR_WORKSPACE;
+  Work probe;
+  size_t need = carve(D, forward, nullptr, &probe);
+  if (ws_bytes < need) return RR_ERR_WORKSPACE;
+  carve(D, forward, ws, W);
+  return RR_OK;
+}
+
+}  // namespace rr
+
+using namespace rr;
+
+extern "C" {
+
+int32_t rr_capacity(int32_t T, int32_t E, float capacity_factor) {
+  if (T <= 0 || E <= 0 || !(capacity_factor > 0.0f) || !isfinite(capacity_factor)) return -1;
+  double c = ceil((double)capacity_factor * (double)T / (double)E);
+  if (c < 1.0) c = 1.0;
+  if (c > 2147483647.0) return -1;
+  return (int32_t)c;
+}
+
+int rr_workspace_bytes(const rr_config *cfg, size_t *bytes) {
+  if (!bytes) return RR_ERR_INVALID_ARG;
+  Dims D;
+  int rc = make_dims(cfg, cfg && cfg->d_ff > 0, &D);
+  if (rc != RR_OK) return rc;
+  Work W;
+  *bytes = carve(D, D.F > 0, nullptr, &W);
+  return RR_OK;
+}
+
+int rr_router_scores(const rr_config *cfg, const void *x, const float *w_router, const float *bias, float *logits,
+                     float *probs, int32_t *rank_expert, void *stream) {
+  Dims D;
+  int rc = make_dims(cfg, false, &D);
+  if (rc != RR_OK) return rc;
+  if (!x || !w_router || !logits) return RR_ERR_INVALID_ARG;
+  hipError_t e = launch_router(D, x, w_router, bias, logits, probs, rank_expert, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? RR_OK : RR_ERR_HIP;
+}
+
+int rr_rectified_dispatch(const rr_config *cfg, const float *logits, const rr_tables *out, void *workspace,
+                          size_t workspace_bytes, void *stream) {
+  Dims D;
+  int rc = make_dims(cfg, false, &D);
+  if (rc != RR_OK) return rc;
+  if (!logits || !tables_complete(out)) return RR_ERR_INVALID_ARG;
+  Work W;
+  memset(&W, 0, sizeof(W));
+  rc = check_ws(D, false, workspace, workspace_bytes, &W);
+  if (rc != RR_OK) return rc;
+  hipError_t e = launch_dispatch(D, logits, *out, W, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? RR_OK : RR_ERR_HIP;
+}
+
+int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, const float *bias, const void *w1,
+                   const void *w3, const void *w2, void *out, const rr_tables *tables, float *logits,
+                   void *workspace, size_t workspace_bytes, void *stream) {
+  Dims D;
+  int rc = make_dims(cfg, true, &D);
+  if (rc != RR_OK) return rc;
+  if (!x || !w_router || !w1 || !w2 || !out) return RR_ERR_INVALID_ARG;
+  if (cfg->act == RR_ACT_SWIGLU && !w3) return RR_ERR_INVALID_ARG;
+  if (tables && !tables_complete(tables)) return RR_ERR_INVALID_ARG;
+  Work W;
+  memset(&W, 0, sizeof(W));
+  rc = check_ws(D, true, workspace, workspace_bytes, &W);
+  if (rc != RR_OK) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const rr_tables &tb = tables ? *tables : W.tables;
+  float *lg = logits ? logits : W.logits;
+  hipError_t e = launch_router(D, x, w_router, bias, lg, nullptr, nullptr, s);
+  if (e == hipSuccess) e = launch_dispatch(D, lg, tb, W, s);
+  if (e == hipSuccess) e = launch_gather(D, x, tb, W, s);
+  if (e == hipSuccess) e = launch_ffn(D, w1, w3, w2, W, s);
+  if (e == hipSuccess) e = launch_combine(D, tb, W, out, s);
+  return e == hipSuccess ? RR_OK : RR_ERR_HIP;
+}
+
+int rr_profile_enable(int on) {
+  g_prof_on = on != 0;
+  return RR_OK;
+}
+
+int rr_profile_read(rr_kernel_time *out, int32_t max_entries, int32_t *n_entries) {
+  if (!out || !n_entries || max_entries < K_COUNT) return RR_ERR_INVALID_ARG;
+  if (hipDeviceSynchronize() != hipSuccess) return RR_ERR_HIP;
+  for (int i = 0; i < K_COUNT; ++i) out[i] = {g_kernel_names[i], 0, 0.0f};
+  for (const ProfSpan &sp : g_spans) {
+    float ms = 0.0f;
+    if (hipEventElapsedTime(&ms, sp.a, sp.b) == hipSuccess) {
+      out[sp.id].launches += 1;
+      out[sp.id].total_ms += ms;
+    }
+    g_free_events.push_back(sp.a);
+    g_free_events.push_back(sp.b);
+  }
+  g_spans.clear();
+  *n_entries = K_COUNT;
+  return RR_OK;
+}
+
+const char *rr_strerror(int code) {
+  switch (code) {
+    case RR_OK: return "ok";
+    case RR_ERR_INVALID_ARG: return "invalid argument";
+    case RR_ERR_UNSUPPORTED: return "unsupported configuration";
+    case RR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case RR_ERR_HIP: return "HIP runtime or launch failure";
+    default: return "unknown rr_status";
+  }
+}
+
+}  // extern "C"

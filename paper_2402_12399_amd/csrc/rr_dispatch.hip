@@ -1,0 +1,465 @@
+// Capacity-limited top-k slotting (Sec. 3), Intra-GPU Rectification (Sec. 4.1), Fill-in
+// Rectification (Sec. 4.2) and the Eq. 2 / Eq. 3 combine weights: logits -> tables.
+//
+// Structure.  The number of tokens an expert keeps in round r depends only on how many candidates
+// it received in rounds 0..r (kept = min(candidates, C - filled)), never on WHICH ones were kept.
+// So all k top-k rounds and the Fill-in round (the (k+1)-th round at unchanged capacity, Sec. 4.2)
+// are planned from candidate counts alone and then resolved concurrently, one workgroup per
+// (round, expert) list:
+//   topk_rank          per token: ranked experts, score keys, best expert of its own group,
+//                      candidate counts per (list, token block)
+//   scan_candidates    exclusive scan of those counts over token blocks, per list
+//   plan_rounds        per expert: kept counts and first free slot of every round
+//   scatter_candidates stable split of the tokens into per-list arrays (ascending token index)
+//   select_slot        per list: radix-select the score threshold of the kept set (ties -> lower
+//                      token index), then a prefix scan in token order hands out consecutive slots
+//   ir_count / ir_scan / row_plan / ir_weights
+//                      per-expert Intra-GPU lists (stable, token order), dispatched-row layout and
+//                      row tiles for the grouped GEMM, combine weights
+// Every table is a deterministic function of the logits: integer atomics are only used for counts.
+#include "rr_device.h"
+
+namespace rr {
+
+namespace {
+
+constexpr int TS = kMaxE + 1;  // LDS row stride of a [token][expert] tile
+
+struct DispatchArgs {
+  int T, E, k, C, NR, NCAT, NB, Eg, Tg, ir, fr, arrival, BM, max_mtiles;
+};
+
+// lanes of this wave whose (valid, e) equals the caller's; e < 64
+__device__ inline unsigned long long same_expert_mask(bool valid, int e) {
+  unsigned long long mask = __ballot(valid);
+#pragma unroll
+  for (int b = 0; b < 6; ++b) {
+    bool bit = (e >> b) & 1;
+    unsigned long long bb = __ballot(valid && bit);
+    mask &= bit ? bb : ~bb;
+  }
+  return mask;
+}
+
+__device__ inline int lanes_below(unsigned long long mask) {
+  int lane = lane_id();
+  return __popcll(mask & ((1ull << lane) - 1ull));
+}
+
+// ------------------------------------------------------------------ topk_rank
+__global__ __launch_bounds__(kTokBlock) void topk_rank_kernel(const float *__restrict__ logits, DispatchArgs A,
+                                                              int32_t *__restrict__ rank_expert,
+                                                              int32_t *__restrict__ slot, u32 *__restrict__ key,
+                                                              float *__restrict__ ir_score,
+                                                              int32_t *__restrict__ ir_cand,
+                                                              int32_t *__restrict__ blk_cnt) {
+  __shared__ float tile[kTokBlock * TS];
+  __shared__ int cnt[kMaxRounds * kMaxE];
+  const int tid = threadIdx.x, b = blockIdx.x;
+  const int t0 = b * kTokBlock;
+  const int ntok = min(kTokBlock, A.T - t0);
+  const int E = A.E;
+  const float *src = logits + (size_t)t0 * E;
+  for (int idx = tid; idx < ntok * E; idx += kTokBlock) {
+    int row = idx / E, e = idx - row * E;
+    tile[row * TS + e] = src[idx];
+  }
+  for (int c = tid; c < A.NCAT; c += kTokBlock) cnt[c] = 0;
+  __syncthreads();
+  if (tid < ntok) {
+    const int i = t0 + tid;
+    const float *row = tile + tid * TS;
+    float bs[kMaxRank];
+    int be[kMaxRank];
+    const int n = min(A.k + 1, E);
+    top_n_of_row(row, E, n, bs, be);
+#pragma unroll
+    for (int q = 0; q < kMaxRank; ++q) {
+      if (q <= A.k) rank_expert[(size_t)i * (A.k + 1) + q] = (q < n) ? be[q] : -1;
+      if (q < A.NR) {
+        key[(size_t)i * A.NR + q] = score_key(bs[q]);
+        atomicAdd(&cnt[q * E + be[q]], 1);
+      }
+    }
+    if (!A.fr) slot[(size_t)i * (A.k + 1) + A.k] = -1;
+    const int g = i / A.Tg;
+    float best;
+    int arg;
+    best_in_group(row, g * A.Eg, (g + 1) * A.Eg, best, arg);
+    ir_score[i] = best;
+    ir_cand[i] = arg;
+  }
+  __syncthreads();
+  for (int c = tid; c < A.NCAT; c += kTokBlock) blk_cnt[(size_t)c * A.NB + b] = cnt[c];
+}
+
+// ------------------------------------------------------------------ scan over token blocks
+// One workgroup per list: exclusive scan of a[list][0..NB) in place, total to tot[list].
+__global__ __launch_bounds__(256) void scan_blocks_kernel(int32_t *__restrict__ a, int32_t *__restrict__ tot, int NB) {
+  __shared__ int wsum[4];
+  int32_t *p = a + (size_t)blockIdx.x * NB;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  int running = 0;
+  for (int base = 0; base < NB; base += 256) {
+    int idx = base + tid;
+    int v = idx < NB ? p[idx] : 0;
+    int incl = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      int t = __shfl_up(incl, off);
+      if (lane >= off) incl += t;
+    }
+    if (lane == 63) wsum[w] = incl;
+    __syncthreads();
+    int before = 0, total = 0;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      int s = wsum[q];
+      if (q < w) before += s;
+      total += s;
+    }
+    if (idx < NB) p[idx] = running + before + incl - v;
+    running += total;
+    __syncthreads();
+  }
+  if (tid == 0) tot[blockIdx.x] = running;
+}
+
+// ------------------------------------------------------------------ plan_rounds
+__global__ __launch_bounds__(64) void plan_rounds_kernel(DispatchArgs A, const int32_t *__restrict__ cat_cnt,
+                                                         int32_t *__restrict__ cat_m, int32_t *__restrict__ cat_fill0,
+                                                         int32_t *__restrict__ cat_base,
+                                                         int32_t *__restrict__ fill_topk,
+                                                         int32_t *__restrict__ fill_total) {
+  const int j = threadIdx.x;
+  if (j < A.E) {
+    int fill = 0;
+    for (int r = 0; r < A.NR; ++r) {
+      int c = r * A.E + j;
+      int m = min(cat_cnt[c], A.C - fill);
+      cat_m[c] = m;
+      cat_fill0[c] = fill;
+      fill += m;
+      if (r == A.k - 1) fill_topk[j] = fill;
+    }
+    fill_total[j] = fill;
+  }
+  if (j < A.NR) {
+    int base = j * A.T;  // every token is a candidate of exactly one list per round
+    for (int e = 0; e < A.E; ++e) {
+      cat_base[j * A.E + e] = base;
+      base += cat_cnt[j * A.E + e];
+    }
+  }
+}
+
+// ------------------------------------------------------------------ scatter_candidates
+__global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchArgs A,
+                                                                       const int32_t *__restrict__ rank_expert,
+                                                                       const u32 *__restrict__ key,
+                                                                       const int32_t *__restrict__ blk_off,
+                                                                       const int32_t *__restrict__ cat_base,
+                                                                       u32 *__restrict__ cand_key,
+                                                                       int32_t *__restrict__ cand_tok) {
+  constexpr int NW = kTokBlock / kWave;
+  __shared__ int wcnt[kMaxRounds][NW][kMaxE];
+  const int tid = threadIdx.x, b = blockIdx.x, w = tid >> 6;
+  const int i = b * kTokBlock + tid;
+  const bool valid = i < A.T;
+  for (int c = tid; c < kMaxRounds * NW * kMaxE; c += kTokBlock) (&wcnt[0][0][0])[c] = 0;
+  __syncthreads();
+  int e_r[kMaxRounds], rank_r[kMaxRounds];
+#pragma unroll
+  for (int r = 0; r < kMaxRounds; ++r) {
+    e_r[r] = 0;
+    rank_r[r] = 0;
+    if (r < A.NR) {
+      int e = valid ? rank_expert[(size_t)i * (A.k + 1) + r] : 0;
+      unsigned long long mask = same_expert_mask(valid, e);
+      int below = lanes_below(mask);
+      if (valid && below == 0) wcnt[r][w][e] = __popcll(mask);
+      e_r[r] = e;
+      rank_r[r] = below;
+    }
+  }
+  __syncthreads();
+  if (!valid) return;
+#pragma unroll
+  for (int r = 0; r < kMaxRounds; ++r) {
+    if (r < A.NR) {
+      int e = e_r[r], cat = r * A.E + e;
+      int pos = cat_base[cat] + blk_off[(size_t)cat * A.NB + b] + rank_r[r];
+      for (int q = 0; q < w; ++q) pos += wcnt[r][q][e];
+      cand_key[pos] = key[(size_t)i * A.NR + r];
+      cand_tok[pos] = i;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ select_slot
+constexpr int SS_THREADS = 1024;
+constexpr int SS_WAVES = SS_THREADS / kWave;
+
+__global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A, const int32_t *__restrict__ cat_cnt,
+                                                                 const int32_t *__restrict__ cat_m,
+                                                                 const int32_t *__restrict__ cat_fill0,
+                                                                 const int32_t *__restrict__ cat_base,
+                                                                 const u32 *__restrict__ cand_key,
+                                                                 const int32_t *__restrict__ cand_tok,
+                                                                 int32_t *__restrict__ slot,
+                                                                 int32_t *__restrict__ slot_token) {
+  __shared__ u32 hist[256];
+  __shared__ u32 s_bucket, s_remaining;
+  __shared__ int wtot[SS_WAVES][2];
+  const int cat = blockIdx.x, r = cat / A.E, j = cat - r * A.E;
+  const int n = cat_cnt[cat], m = cat_m[cat], fill0 = cat_fill0[cat];
+  const u32 *keys = cand_key + cat_base[cat];
+  const int32_t *toks = cand_tok + cat_base[cat];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const bool by_score = !A.arrival || r == A.k;  // the Fill-in round always selects by score (Sec. 4.2)
+
+  // mode 0: nobody kept; 1: everybody kept; 2: the first m in token order; 3: by score threshold
+  int mode = m == 0 ? 0 : (m == n ? 1 : (by_score ? 3 : 2));
+  u32 thr = 0, need_eq = 0;
+  if (mode == 3) {
+    // m-th largest key by 8-bit digits from the top; `remaining` = how many are still to be taken
+    // from the keys that match the digits fixed so far
+    u32 prefix = 0, remaining = (u32)m;
+    for (int pass = 3; pass >= 0; --pass) {
+      const int shift = pass * 8;
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int idx = tid; idx < n; idx += SS_THREADS) {
+        u32 kx = keys[idx];
+        bool match = pass == 3 || ((kx ^ prefix) >> (shift + 8)) == 0;
+        if (match) atomicAdd(&hist[(kx >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      if (w == 0) {
+        // lane l owns bins 255-4l .. 252-4l, i.e. bins in descending order across lanes
+        u32 c0 = hist[255 - 4 * lane], c1 = hist[254 - 4 * lane], c2 = hist[253 - 4 * lane], c3 = hist[252 - 4 * lane];
+        u32 s = c0 + c1 + c2 + c3, incl = s;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+          u32 t = __shfl_up(incl, off);
+          if (lane >= off) incl += t;
+        }
+        u32 excl = incl - s;
+        if (excl < remaining && remaining <= incl) {
+          u32 rem = remaining - excl;
+          int bkt = 255 - 4 * lane;
+          if (rem > c0) { rem -= c0; --bkt;
+            if (rem > c1) { rem -= c1; --bkt;
+              if (rem > c2) { rem -= c2; --bkt; } } }
+          s_bucket = (u32)bkt;
+          s_remaining = rem;
+        }
+      }
+      __syncthreads();
+      prefix |= s_bucket << shift;
+      remaining = s_remaining;
+      __syncthreads();
+    }
+    thr = prefix;
+    need_eq = remaining;  // of the keys equal to thr, the first need_eq in token order are kept
+  }
+
+  int run_gt = 0, run_eq = 0;
+  for (int base = 0; base < n; base += SS_THREADS) {
+    const int idx = base + tid;
+    const bool valid = idx < n;
+    u32 kx = 0;
+    int tok = 0;
+    if (valid) { kx = keys[idx]; tok = toks[idx]; }
+    bool gt, eq = false;
+    if (mode == 3) { gt = valid && kx > thr; eq = valid && kx == thr; }
+    else if (mode == 2) gt = valid && idx < m;
+    else gt = valid && mode == 1;
+    unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+    unsigned long long below = (1ull << lane) - 1ull;
+    int gt_before = __popcll(bgt & below), eq_before = __popcll(beq & below);
+    if (lane == 0) { wtot[w][0] = __popcll(bgt); wtot[w][1] = __popcll(beq); }
+    __syncthreads();
+    int tot_gt = 0, tot_eq = 0;
+#pragma unroll
+    for (int q = 0; q < SS_WAVES; ++q) {
+      int a = wtot[q][0], c = wtot[q][1];
+      if (q < w) { gt_before += a; eq_before += c; }
+      tot_gt += a; tot_eq += c;
+    }
+    if (valid) {
+      int eqs = run_eq + eq_before;                       // equal keys before this one
+      bool kept = gt || (eq && (u32)eqs < need_eq);
+      int kept_before = run_gt + gt_before + min(eqs, (int)need_eq);
+      int s = fill0 + kept_before;
+      slot[(size_t)tok * (A.k + 1) + r] = kept ? s : -1;
+      if (kept) slot_token[(size_t)j * A.C + s] = tok;
+    }
+    run_gt += tot_gt;
+    run_eq += tot_eq;
+    __syncthreads();
+  }
+  // the last round of an expert pads the rest of its queue (Sec. 3: zero padding)
+  if (r == A.NR - 1)
+    for (int s = fill0 + m + tid; s < A.C; s += SS_THREADS) slot_token[(size_t)j * A.C + s] = -1;
+}
+
+// ------------------------------------------------------------------ Intra-GPU lists
+__device__ inline int drops_of_token(const int32_t *slot, int i, int k) {
+  int n = 0;
+  for (int r = 0; r < k; ++r) n += slot[(size_t)i * (k + 1) + r] < 0;
+  return n;
+}
+
+__global__ __launch_bounds__(kTokBlock) void ir_count_kernel(DispatchArgs A, const int32_t *__restrict__ slot,
+                                                             const int32_t *__restrict__ ir_cand,
+                                                             int32_t *__restrict__ ir_blk_cnt) {
+  __shared__ int cnt[kMaxE];
+  const int tid = threadIdx.x, b = blockIdx.x;
+  const int i = b * kTokBlock + tid;
+  if (tid < kMaxE) cnt[tid] = 0;
+  __syncthreads();
+  if (i < A.T && drops_of_token(slot, i, A.k) > 0) atomicAdd(&cnt[ir_cand[i]], 1);
+  __syncthreads();
+  if (tid < A.E) ir_blk_cnt[(size_t)tid * A.NB + b] = cnt[tid];
+}
+
+// Dispatched-row layout: expert e owns rows [row_base[e], row_base[e+1]): its occupied capacity
+// slots first, then its Intra-GPU rows.  Also cuts every expert's rows into tiles of BM rows.
+__global__ __launch_bounds__(64) void row_plan_kernel(DispatchArgs A, const int32_t *__restrict__ fill_total,
+                                                      const int32_t *__restrict__ ir_cnt,
+                                                      int32_t *__restrict__ ir_offset, int32_t *__restrict__ row_base,
+                                                      int32_t *__restrict__ tile_expert,
+                                                      int32_t *__restrict__ tile_row0, int32_t *__restrict__ n_tiles) {
+  if (threadIdx.x != 0) return;
+  int off = 0, base = 0, nt = 0;
+  for (int e = 0; e < A.E; ++e) {
+    int nir = A.ir ? ir_cnt[e] : 0;
+    ir_offset[e] = off;
+    row_base[e] = base;
+    int rows = fill_total[e] + nir;
+    for (int m0 = 0; m0 < rows && nt < A.max_mtiles; m0 += A.BM) {
+      tile_expert[nt] = e;
+      tile_row0[nt] = m0;
+      ++nt;
+    }
+    off += nir;
+    base += rows;
+  }
+  ir_offset[A.E] = off;
+  row_base[A.E] = base;
+  *n_tiles = nt;
+}
+
+// Per token: Intra-GPU list position (Sec. 4.1) and the Eq. 2 / Eq. 3 weights.
+__global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, const int32_t *__restrict__ slot,
+                                                               const u32 *__restrict__ key,
+                                                               const float *__restrict__ ir_score,
+                                                               const int32_t *__restrict__ ir_cand,
+                                                               const int32_t *__restrict__ ir_blk_off,
+                                                               const int32_t *__restrict__ ir_offset,
+                                                               int32_t *__restrict__ ir_expert,
+                                                               int32_t *__restrict__ ir_row,
+                                                               int32_t *__restrict__ ir_token,
+                                                               float *__restrict__ combine_w) {
+  constexpr int NW = kTokBlock / kWave;
+  __shared__ int wcnt[NW][kMaxE];
+  const int tid = threadIdx.x, b = blockIdx.x, w = tid >> 6;
+  const int i = b * kTokBlock + tid;
+  const bool valid = i < A.T;
+  for (int c = tid; c < NW * kMaxE; c += kTokBlock) (&wcnt[0][0])[c] = 0;
+  __syncthreads();
+  int ndrop = 0;
+  if (valid) ndrop = drops_of_token(slot, i, A.k);
+  const bool has_ir = valid && A.ir && ndrop > 0;
+  const int h = has_ir ? ir_cand[i] : 0;
+  unsigned long long mask = same_expert_mask(has_ir, h);
+  const int below = lanes_below(mask);
+  if (has_ir && below == 0) wcnt[w][h] = __popcll(mask);
+  __syncthreads();
+  if (!valid) return;
+  float a_h = 0.0f;
+  if (has_ir) {
+    int row = ir_blk_off[(size_t)h * A.NB + b] + below;
+    for (int q = 0; q < w; ++q) row += wcnt[q][h];
+    ir_expert[i] = h;
+    ir_row[i] = row;
+    ir_token[ir_offset[h] + row] = i;
+    a_h = ir_score[i];
+  } else {
+    ir_expert[i] = -1;
+    ir_row[i] = -1;
+  }
+  // Eq. 2 / Eq. 3: softmax over the successfully routed experts, a placed Fill-in expert, and the
+  // Intra-GPU expert counted (k - |R_i|) times
+  float a_r[kMaxRank];
+  bool kept[kMaxRank];
+  float mx = has_ir ? a_h : -INFINITY;
+#pragma unroll
+  for (int r = 0; r < kMaxRank; ++r) {
+    kept[r] = false;
+    a_r[r] = 0.0f;
+    if (r < A.NR) {
+      kept[r] = slot[(size_t)i * (A.k + 1) + r] >= 0;
+      if (kept[r]) {
+        a_r[r] = key_score(key[(size_t)i * A.NR + r]);
+        mx = fmaxf(mx, a_r[r]);
+      }
+    }
+  }
+  float term[kMaxRank], t_ir = has_ir ? (float)ndrop * expf(a_h - mx) : 0.0f, Z = t_ir;
+#pragma unroll
+  for (int r = 0; r < kMaxRank; ++r) {
+    term[r] = kept[r] ? expf(a_r[r] - mx) : 0.0f;
+    Z += term[r];
+  }
+  const float inv = Z > 0.0f ? 1.0f / Z : 0.0f;
+  float *cw = combine_w + (size_t)i * (A.k + 2);
+#pragma unroll
+  for (int r = 0; r < kMaxRank; ++r)
+    if (r <= A.k) cw[r] = term[r] * inv;
+  cw[A.k + 1] = t_ir * inv;
+}
+
+}  // namespace
+
+hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, hipStream_t s) {
+  DispatchArgs A{D.T, D.E, D.k, D.C, D.NR, D.NCAT, D.NB, D.Eg, D.Tg, D.ir, D.fr, D.arrival, D.BM, D.max_mtiles};
+  prof_begin(K_TOPK, s);
+  topk_rank_kernel<<<D.NB, kTokBlock, 0, s>>>(logits, A, tb.rank_expert, tb.slot, W.key, W.ir_score, W.ir_cand,
+                                              W.blk_cnt);
+  prof_end(K_TOPK, s);
+  prof_begin(K_SCAN_CAND, s);
+  scan_blocks_kernel<<<D.NCAT, 256, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NB);
+  prof_end(K_SCAN_CAND, s);
+  prof_begin(K_PLAN, s);
+  plan_rounds_kernel<<<1, 64, 0, s>>>(A, W.cat_cnt, W.cat_m, W.cat_fill0, W.cat_base, tb.fill_topk, tb.fill_total);
+  prof_end(K_PLAN, s);
+  prof_begin(K_SCATTER_CAND, s);
+  scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_base, W.cand_key,
+                                                       W.cand_tok);
+  prof_end(K_SCATTER_CAND, s);
+  prof_begin(K_SELECT_SLOT, s);
+  select_slot_kernel<<<D.NCAT, SS_THREADS, 0, s>>>(A, W.cat_cnt, W.cat_m, W.cat_fill0, W.cat_base, W.cand_key,
+                                                   W.cand_tok, tb.slot, tb.slot_token);
+  prof_end(K_SELECT_SLOT, s);
+  if (D.ir) {
+    prof_begin(K_IR_COUNT, s);
+    ir_count_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.ir_cand, W.ir_blk_cnt);
+    prof_end(K_IR_COUNT, s);
+    prof_begin(K_IR_SCAN, s);
+    scan_blocks_kernel<<<D.E, 256, 0, s>>>(W.ir_blk_cnt, W.ir_cnt, D.NB);
+    prof_end(K_IR_SCAN, s);
+  }
+  prof_begin(K_ROW_PLAN, s);
+  row_plan_kernel<<<1, 64, 0, s>>>(A, tb.fill_total, W.ir_cnt, tb.ir_offset, W.row_base, W.tile_expert, W.tile_row0,
+                                   W.n_tiles);
+  prof_end(K_ROW_PLAN, s);
+  prof_begin(K_IR_WEIGHTS, s);
+  ir_weights_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.key, W.ir_score, W.ir_cand, W.ir_blk_cnt, tb.ir_offset,
+                                               tb.ir_expert, tb.ir_row, tb.ir_token, tb.combine_w);
+  prof_end(K_IR_WEIGHTS, s);
+  return hipGetLastError();
+}
+
+}  // namespace rr

@@ -1,0 +1,332 @@
+// Expert FFN as a grouped GEMM over the dispatched rows (Sec. 5.1: every expert is a LLaMA FFN):
+//   up   : h[row, f] = silu(x_disp[row] . W1_e[f]) * (x_disp[row] . W3_e[f])      (SwiGLU)
+//          h[row, f] = gelu(x_disp[row] . W1_e[f])                                 (GELU)
+//   down : y[row, c] = h[row] . W2_e[c]
+// Both are "A[rows,K] times B[N,K]^T" with K contiguous in both operands; rows of expert e are
+// row_base[e] .. row_base[e+1]-1 and are cut into row tiles by row_plan (tile_expert, tile_row0).
+//
+// bf16 path: v_mfma_f32_32x32x16_bf16, fp32 accumulate.  A workgroup of 4 waves owns a BM x BN
+// output tile; K advances in chunks of 64 through double-buffered LDS (global -> registers -> LDS
+// overlapped with the MFMAs of the previous chunk).  LDS rows are 128 B; the 16-byte chunk c of
+// row r lives at chunk position c ^ (r & 7), which makes both the row-wise stores and the
+// fragment loads (32 rows x one chunk) conflict-free.
+// fp32 path (tiny fp32 workload): plain FMA tiles, fp32 throughout.
+#include "rr_device.h"
+
+namespace rr {
+
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+
+__device__ inline u32 f32_to_bf16_bits(float f) {
+  u32 u = __builtin_bit_cast(u32, f);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+
+__device__ inline float silu(float g) { return g / (1.0f + __expf(-g)); }
+__device__ inline float gelu_erf(float g) { return 0.5f * g * (1.0f + erff(g * 0.70710678118654752f)); }
+
+constexpr int GB_THREADS = 256;
+constexpr int GB_BK = 64;             // bf16 elements per K chunk = 128 B per LDS row
+constexpr int GB_ROW_BYTES = 128;
+
+struct GemmArgs {
+  const void *A;        // [rows, K]
+  const void *B0;       // [E, N, K]
+  const void *B1;       // [E, N, K] gated only
+  void *Cout;           // [rows, N]
+  int K, N;
+  int NT;               // column tiles; workgroup id = row tile * NT + column tile
+  const int32_t *row_base, *tile_expert, *tile_row0, *n_tiles;
+};
+
+// WAVES_M x WAVES_N waves, each owning WM x WN fragments of 32x32.
+// GATED: the staged B rows are [BN gate rows | BN up rows] with BN = BROWS / 2, and a wave's
+// fragments j < WN/2 are gate columns, j >= WN/2 the matching up columns.
+template <int WAVES_M, int WAVES_N, int WM, int WN, bool GATED, int ACT>
+__global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(GemmArgs P) {
+  static_assert(WAVES_M * WAVES_N == 4, "four waves");
+  constexpr int BM = WAVES_M * WM * 32;
+  constexpr int BROWS = WAVES_N * WN * 32;
+  constexpr int BN = GATED ? BROWS / 2 : BROWS;
+  constexpr int A_LD = BM / 32;       // 16-byte loads per thread per chunk
+  constexpr int B_LD = BROWS / 32;
+  constexpr int STAGE_BYTES = (BM + BROWS) * GB_ROW_BYTES;
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int mt = blockIdx.x / P.NT;
+  if (mt >= *P.n_tiles) return;
+  const int e = P.tile_expert[mt];
+  const int m0 = P.tile_row0[mt];
+  const int rbase = P.row_base[e];
+  const int rows_e = P.row_base[e + 1] - rbase;
+  const int n0 = (blockIdx.x - mt * P.NT) * BN;
+  const int K = P.K, N = P.N;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int wm = w / WAVES_N, wn = w % WAVES_N;
+
+  const char *Ab = static_cast<const char *>(P.A);
+  const char *B0b = static_cast<const char *>(P.B0) + (size_t)e * N * K * 2;
+  const char *B1b = GATED ? static_cast<const char *>(P.B1) + (size_t)e * N * K * 2 : nullptr;
+
+  // per-thread global sources: chunk id q = tid + 256 i -> row q / 8, chunk q % 8
+  const int lc = tid & 7;
+  const char *a_src[A_LD];
+  const char *b_src[B_LD];
+  int lds_off_a[A_LD], lds_off_b[B_LD];
+#pragma unroll
+  for (int i = 0; i < A_LD; ++i) {
+    int r = (tid >> 3) + 32 * i;
+    int gr = min(m0 + r, rows_e - 1);
+    a_src[i] = Ab + ((size_t)(rbase + gr) * K + lc * 8) * 2;
+    lds_off_a[i] = r * GB_ROW_BYTES + ((lc ^ (r & 7)) << 4);
+  }
+#pragma unroll
+  for (int i = 0; i < B_LD; ++i) {
+    int r = (tid >> 3) + 32 * i;
+    const char *bb = B0b;
+    int nr = r;
+    if (GATED && r >= BN) { bb = B1b; nr = r - BN; }
+    int gn = min(n0 + nr, N - 1);
+    b_src[i] = bb + ((size_t)gn * K + lc * 8) * 2;
+    lds_off_b[i] = BM * GB_ROW_BYTES + r * GB_ROW_BYTES + ((lc ^ (r & 7)) << 4);
+  }
+
+  f32x16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  uint4 ra[A_LD], rb[B_LD];
+  const int KT = (K + GB_BK - 1) / GB_BK;
+  auto load_global = [&](int kt) {
+    const int kbyte = kt * GB_BK * 2;
+    const bool in = (kt * GB_BK + lc * 8) < K;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) ra[i] = in ? *reinterpret_cast<const uint4 *>(a_src[i] + kbyte) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) rb[i] = in ? *reinterpret_cast<const uint4 *>(b_src[i] + kbyte) : make_uint4(0, 0, 0, 0);
+  };
+  auto store_lds = [&](int buf) {
+    char *st = smem + buf * STAGE_BYTES;
+#pragma unroll
+    for (int i = 0; i < A_LD; ++i) *reinterpret_cast<uint4 *>(st + lds_off_a[i]) = ra[i];
+#pragma unroll
+    for (int i = 0; i < B_LD; ++i) *reinterpret_cast<uint4 *>(st + lds_off_b[i]) = rb[i];
+  };
+
+  // fragment addressing: lane reads row (lane & 31), chunk 2*ks + (lane >> 5)
+  const int fr = lane & 31, fh = lane >> 5;
+  int a_row_off[WM], b_row_off[WN], a_sw[WM], b_sw[WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    int r = (wm * WM + i) * 32 + fr;
+    a_row_off[i] = r * GB_ROW_BYTES;
+    a_sw[i] = r & 7;
+  }
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    int r;
+    if (GATED) {
+      constexpr int H = WN / 2;
+      r = (j < H) ? (wn * H + j) * 32 + fr : BN + (wn * H + (j - H)) * 32 + fr;
+    } else {
+      r = (wn * WN + j) * 32 + fr;
+    }
+    b_row_off[j] = BM * GB_ROW_BYTES + r * GB_ROW_BYTES;
+    b_sw[j] = r & 7;
+  }
+
+  load_global(0);
+  store_lds(0);
+  __syncthreads();
+  for (int kt = 0; kt < KT; ++kt) {
+    if (kt + 1 < KT) load_global(kt + 1);
+    const char *st = smem + (kt & 1) * STAGE_BYTES;
+#pragma unroll
+    for (int ks = 0; ks < GB_BK / 16; ++ks) {
+      bf16x8 af[WM], bfr[WN];
+      const int c = 2 * ks + fh;
+#pragma unroll
+      for (int i = 0; i < WM; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(st + a_row_off[i] + ((c ^ a_sw[i]) << 4));
+#pragma unroll
+      for (int j = 0; j < WN; ++j) bfr[j] = *reinterpret_cast<const bf16x8 *>(st + b_row_off[j] + ((c ^ b_sw[j]) << 4));
+#pragma unroll
+      for (int i = 0; i < WM; ++i)
+#pragma unroll
+        for (int j = 0; j < WN; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < KT) store_lds((kt + 1) & 1);
+    __syncthreads();
+  }
+
+  // epilogue: accumulator element v of a 32x32 fragment is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
+  uint16_t *Cb = static_cast<uint16_t *>(P.Cout);
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    const int frag_row0 = m0 + (wm * WM + i) * 32 + 4 * fh;
+    if (GATED) {
+      constexpr int H = WN / 2;
+#pragma unroll
+      for (int j = 0; j < H; ++j) {
+        const int col = n0 + (wn * H + j) * 32 + fr;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = frag_row0 + 8 * (v >> 2) + (v & 3);
+          if (row < rows_e && col < N) {
+            float g = acc[i][j][v], u = acc[i][j + H][v];
+            Cb[(size_t)(rbase + row) * N + col] = (uint16_t)f32_to_bf16_bits(silu(g) * u);
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < WN; ++j) {
+        const int col = n0 + (wn * WN + j) * 32 + fr;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = frag_row0 + 8 * (v >> 2) + (v & 3);
+          if (row < rows_e && col < N) {
+            float c = acc[i][j][v];
+            if (ACT == RR_ACT_GELU) c = gelu_erf(c);
+            Cb[(size_t)(rbase + row) * N + col] = (uint16_t)f32_to_bf16_bits(c);
+          }
+        }
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------ fp32 path
+constexpr int GF_BM = 64, GF_BN = 64, GF_BK = 16, GF_LD = GF_BM + 4;
+
+// ACT: -1 none, RR_ACT_GELU, RR_ACT_SWIGLU (gated: B0 = gate, B1 = up)
+template <int ACT>
+__global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs P) {
+  constexpr bool GATED = ACT == RR_ACT_SWIGLU;
+  __shared__ float As[GF_BK][GF_LD], Bs0[GF_BK][GF_LD], Bs1[GATED ? GF_BK : 1][GF_LD];
+  const int mt = blockIdx.x / P.NT;
+  if (mt >= *P.n_tiles) return;
+  const int e = P.tile_expert[mt];
+  const int m0 = P.tile_row0[mt];
+  const int rbase = P.row_base[e];
+  const int rows_e = P.row_base[e + 1] - rbase;
+  const int n0 = (blockIdx.x - mt * P.NT) * GF_BN;
+  const int K = P.K, N = P.N;
+  const float *A = static_cast<const float *>(P.A);
+  const float *B0 = static_cast<const float *>(P.B0) + (size_t)e * N * K;
+  const float *B1 = GATED ? static_cast<const float *>(P.B1) + (size_t)e * N * K : nullptr;
+  const int tid = threadIdx.x, ty = tid >> 4, tx = tid & 15;
+  const int lr = tid >> 2, lc = tid & 3;
+  const float *a_src = A + (size_t)(rbase + min(m0 + lr, rows_e - 1)) * K + lc * 4;
+  const size_t b_off = (size_t)min(n0 + lr, N - 1) * K + lc * 4;
+
+  float g[4][4], u[4][4];
+#pragma unroll
+  for (int a = 0; a < 4; ++a)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) { g[a][b] = 0.0f; u[a][b] = 0.0f; }
+
+  for (int k0 = 0; k0 < K; k0 += GF_BK) {
+    const bool in = k0 + lc * 4 < K;
+    float4 va = in ? *reinterpret_cast<const float4 *>(a_src + k0) : make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 vb = in ? *reinterpret_cast<const float4 *>(B0 + b_off + k0) : make_float4(0.f, 0.f, 0.f, 0.f);
+    As[lc * 4 + 0][lr] = va.x; As[lc * 4 + 1][lr] = va.y; As[lc * 4 + 2][lr] = va.z; As[lc * 4 + 3][lr] = va.w;
+    Bs0[lc * 4 + 0][lr] = vb.x; Bs0[lc * 4 + 1][lr] = vb.y; Bs0[lc * 4 + 2][lr] = vb.z; Bs0[lc * 4 + 3][lr] = vb.w;
+    if (GATED) {
+      float4 vc = in ? *reinterpret_cast<const float4 *>(B1 + b_off + k0) : make_float4(0.f, 0.f, 0.f, 0.f);
+      Bs1[lc * 4 + 0][lr] = vc.x; Bs1[lc * 4 + 1][lr] = vc.y; Bs1[lc * 4 + 2][lr] = vc.z; Bs1[lc * 4 + 3][lr] = vc.w;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < GF_BK; ++kk) {
+      float av[4], bv[4], cv[4];
+#pragma unroll
+      for (int a = 0; a < 4; ++a) av[a] = As[kk][ty * 4 + a];
+#pragma unroll
+      for (int b = 0; b < 4; ++b) { bv[b] = Bs0[kk][tx * 4 + b]; cv[b] = GATED ? Bs1[kk][tx * 4 + b] : 0.0f; }
+#pragma unroll
+      for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+          g[a][b] = fmaf(av[a], bv[b], g[a][b]);
+          if (GATED) u[a][b] = fmaf(av[a], cv[b], u[a][b]);
+        }
+    }
+    __syncthreads();
+  }
+  float *Cf = static_cast<float *>(P.Cout);
+#pragma unroll
+  for (int a = 0; a < 4; ++a) {
+    const int row = m0 + ty * 4 + a;
+    if (row >= rows_e) continue;
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int col = n0 + tx * 4 + b;
+      if (col >= N) continue;
+      float c = g[a][b];
+      if (ACT == RR_ACT_SWIGLU) c = c / (1.0f + expf(-c)) * u[a][b];
+      if (ACT == RR_ACT_GELU) c = gelu_erf(c);
+      Cf[(size_t)(rbase + row) * N + col] = c;
+    }
+  }
+}
+
+template <typename Kern>
+hipError_t set_lds(Kern kern, int bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+}  // namespace
+
+hipError_t launch_ffn(const Dims &D, const void *w1, const void *w3, const void *w2, const Work &W, hipStream_t s) {
+  GemmArgs up{W.x_disp, w1, w3, W.h, D.d, D.F, 0, W.row_base, W.tile_expert, W.tile_row0, W.n_tiles};
+  GemmArgs down{W.h, w2, nullptr, W.y, D.F, D.d, 0, W.row_base, W.tile_expert, W.tile_row0, W.n_tiles};
+  hipError_t err = hipSuccess;
+  if (D.dtype == RR_BF16) {
+    // 256 x 256 staged rows; BM must equal Dims::BM (row tiles are cut by row_plan)
+    constexpr int LDS = 2 * (256 + 256) * GB_ROW_BYTES;
+    auto k_up_gated = gemm_bf16_kernel<2, 2, 4, 4, true, -1>;
+    auto k_up_gelu = gemm_bf16_kernel<2, 2, 4, 4, false, RR_ACT_GELU>;
+    auto k_down = gemm_bf16_kernel<2, 2, 4, 4, false, -1>;
+    static bool attr_done = false;
+    if (!attr_done) {
+      if ((err = set_lds(k_up_gated, LDS)) != hipSuccess) return err;
+      if ((err = set_lds(k_up_gelu, LDS)) != hipSuccess) return err;
+      if ((err = set_lds(k_down, LDS)) != hipSuccess) return err;
+      attr_done = true;
+    }
+    up.NT = D.act == RR_ACT_SWIGLU ? (D.F + 127) / 128 : (D.F + 255) / 256;
+    down.NT = (D.d + 255) / 256;
+    prof_begin(K_FFN_UP, s);
+    if (D.act == RR_ACT_SWIGLU)
+      k_up_gated<<<up.NT * D.max_mtiles, GB_THREADS, LDS, s>>>(up);
+    else
+      k_up_gelu<<<up.NT * D.max_mtiles, GB_THREADS, LDS, s>>>(up);
+    prof_end(K_FFN_UP, s);
+    prof_begin(K_FFN_DOWN, s);
+    k_down<<<down.NT * D.max_mtiles, GB_THREADS, LDS, s>>>(down);
+    prof_end(K_FFN_DOWN, s);
+  } else {
+    up.NT = (D.F + GF_BN - 1) / GF_BN;
+    down.NT = (D.d + GF_BN - 1) / GF_BN;
+    prof_begin(K_FFN_UP, s);
+    if (D.act == RR_ACT_SWIGLU)
+      gemm_f32_kernel<RR_ACT_SWIGLU><<<up.NT * D.max_mtiles, 256, 0, s>>>(up);
+    else
+      gemm_f32_kernel<RR_ACT_GELU><<<up.NT * D.max_mtiles, 256, 0, s>>>(up);
+    prof_end(K_FFN_UP, s);
+    prof_begin(K_FFN_DOWN, s);
+    gemm_f32_kernel<-1><<<down.NT * D.max_mtiles, 256, 0, s>>>(down);
+    prof_end(K_FFN_DOWN, s);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace rr

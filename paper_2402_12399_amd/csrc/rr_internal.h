@@ -1,0 +1,94 @@
+// Internal declarations shared by the HIP translation units of librr.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "rr.h"
+
+namespace rr {
+
+constexpr int kMaxE = 64;
+constexpr int kMaxK = 4;
+constexpr int kMaxRounds = kMaxK + 1;   // k top-k rounds + the Fill-in round
+constexpr int kTokBlock = 128;          // tokens per workgroup in the per-token routing kernels
+constexpr int kWave = 64;
+
+typedef uint32_t u32;
+
+// Everything derived from rr_config on the host.
+struct Dims {
+  int T, d, F, E, k, G, C;
+  int Eg, Tg;
+  int NR;      // routing rounds that place tokens: k (+1 with Fill-in)
+  int NCAT;    // NR * E candidate lists, list id = round * E + expert
+  int NB;      // token blocks of kTokBlock
+  int ir, fr, arrival;
+  int dtype, act;
+  int Rmax;        // upper bound on dispatched rows: min(E*C, NR*T) + (ir ? T : 0)
+  int max_mtiles;  // upper bound on row tiles of the grouped GEMM
+  int BM;          // row-tile height of the grouped GEMM for this dtype
+};
+
+// Device pointers carved out of the caller's workspace.
+struct Work {
+  // routing
+  u32     *key;          // [T, NR]   order-preserving key of the score of the r-th choice
+  float   *ir_score;     // [T]       score of the best expert of the token's own group
+  int32_t *ir_cand;      // [T]       that expert
+  int32_t *blk_cnt;      // [NCAT, NB] candidates per (list, token block); scanned in place
+  int32_t *cat_cnt;      // [NCAT]    candidates per list
+  int32_t *cat_m;        // [NCAT]    how many of them are kept
+  int32_t *cat_fill0;    // [NCAT]    occupied slots of the expert before this round
+  int32_t *cat_base;     // [NCAT]    start of the list in cand_*
+  u32     *cand_key;     // [NR*T]    per-list candidates in ascending token index
+  int32_t *cand_tok;     // [NR*T]
+  int32_t *ir_blk_cnt;   // [E, NB]   Intra-GPU tokens per (expert, token block); scanned in place
+  int32_t *ir_cnt;       // [E]
+  int32_t *row_base;     // [E+1]     first dispatched row of each expert (slot rows, then IR rows)
+  int32_t *tile_expert;  // [max_mtiles] row tiles of the grouped GEMM
+  int32_t *tile_row0;    // [max_mtiles] first row of the tile, relative to row_base[expert]
+  int32_t *n_tiles;      // [1]
+  // forward only
+  float   *logits;       // [T,E] when the caller passes none
+  rr_tables tables;      // storage when the caller passes none
+  void    *x_disp;       // [Rmax, d]
+  void    *h;            // [Rmax, F]
+  void    *y;            // [Rmax, d]
+};
+
+struct Launch {
+  hipStream_t stream;
+};
+
+// Kernel ids for the profiling record.
+enum KernelId {
+  K_ROUTER = 0, K_TOPK, K_SCAN_CAND, K_PLAN, K_SCATTER_CAND, K_SELECT_SLOT,
+  K_IR_COUNT, K_IR_SCAN, K_ROW_PLAN, K_IR_WEIGHTS, K_GATHER, K_FFN_UP, K_FFN_DOWN, K_COMBINE,
+  K_COUNT
+};
+
+void prof_begin(KernelId id, hipStream_t s);
+void prof_end(KernelId id, hipStream_t s);
+
+// Order-preserving map fp32 -> u32 (IEEE '>' on finite floats == '>' on keys; -0.0 and +0.0 share a key).
+__host__ __device__ inline u32 score_key(float a) {
+  u32 u = __builtin_bit_cast(u32, a);
+  if (u == 0x80000000u) u = 0u;
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__host__ __device__ inline float key_score(u32 key) {
+  u32 u = (key & 0x80000000u) ? (key & 0x7fffffffu) : ~key;
+  return __builtin_bit_cast(float, u);
+}
+
+// Stage launchers (each returns a hipError_t from the launches it made).
+hipError_t launch_router(const Dims &D, const void *x, const float *w_router, const float *bias,
+                         float *logits, float *probs, int32_t *rank_expert, hipStream_t s);
+hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, hipStream_t s);
+hipError_t launch_gather(const Dims &D, const void *x, const rr_tables &tb, const Work &W, hipStream_t s);
+hipError_t launch_ffn(const Dims &D, const void *w1, const void *w3, const void *w2, const Work &W, hipStream_t s);
+hipError_t launch_combine(const Dims &D, const rr_tables &tb, const Work &W, void *out, hipStream_t s);
+
+}  // namespace rr

@@ -54,13 +54,10 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def _store(a: np.ndarray, dtype: str):
-    """Round to the storage type.  Returns (storage array, exact float32 view of the stored values)."""
+def _store(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Round to the storage type: float32 as is, bf16 as uint16 bit patterns."""
     a = np.ascontiguousarray(a, dtype=np.float32)
-    if dtype == "f32":
-        return a, a
-    bits = to_bf16_bits(a)
-    return bits, bf16_bits_to_f32(bits)
+    return a if dtype == "f32" else to_bf16_bits(a)
 
 
 def router_bias(w: Workload, rng: np.random.Generator):
@@ -77,30 +74,60 @@ def router_bias(w: Workload, rng: np.random.Generator):
     raise ValueError(w.bias)
 
 
-def make_inputs(w: Workload, with_experts: bool = True, T: int | None = None):
-    """Host arrays for one workload.
+def values_f32(stored: np.ndarray, dtype: str) -> np.ndarray:
+    """Exact float32 values of a storage array (float32, or uint16 bf16 bit patterns)."""
+    return stored if dtype == "f32" else bf16_bits_to_f32(stored)
 
-    Returns a dict with, for x and the expert weights, both the storage array
-    (`x`, `w1`, ... : float32, or uint16 bf16 bit patterns) and the exact float32
-    values those bits represent (`x_f32`, ...).  Router weights and bias are fp32.
+
+def make_inputs(w: Workload, with_experts: bool = True, T: int | None = None):
+    """Host arrays for one workload, drawn with numpy (small and medium workloads).
+
+    x and the expert weights are returned in storage form: float32, or uint16 bf16 bit patterns
+    (see values_f32).  Router weights and bias are fp32.
     """
     T = w.T if T is None else T
     rng = np.random.default_rng(w.seed)
     out = {}
     out["w_router"] = (rng.standard_normal((w.E, w.d_model), dtype=np.float32) * np.float32(0.02))
     out["bias"] = router_bias(w, rng)
-    x = rng.standard_normal((T, w.d_model), dtype=np.float32)
-    out["x"], out["x_f32"] = _store(x, w.dtype)
+    out["x"] = _store(rng.standard_normal((T, w.d_model), dtype=np.float32), w.dtype)
+    out["w1"] = out["w3"] = out["w2"] = None
     if with_experts and w.d_ff > 0:
         shapes = {"w1": (w.E, w.d_ff, w.d_model), "w3": (w.E, w.d_ff, w.d_model), "w2": (w.E, w.d_model, w.d_ff)}
         for name, shp in shapes.items():
             if name == "w3" and w.act != "swiglu":
-                out["w3"], out["w3_f32"] = None, None
                 continue
-            m = np.empty(shp, dtype=np.float32)
-            for e in range(w.E):  # per expert, to bound the temporary
-                m[e] = rng.standard_normal(shp[1:], dtype=np.float32) * np.float32(0.02)
-            out[name], out[name + "_f32"] = _store(m, w.dtype)
+            out[name] = _store(rng.standard_normal(shp, dtype=np.float32) * np.float32(0.02), w.dtype)
+    return out
+
+
+def make_inputs_device(w: Workload, device="cuda", with_experts: bool = True):
+    """Device tensors for one workload, drawn by torch's seeded generator on the GPU.
+
+    Used for the large workloads, where drawing billions of normals on the host would take
+    minutes.  The bits are reproducible for a given torch build and GPU; the CPU oracle is fed by
+    copying the very same bits to the host.  Router weights and bias come from the numpy recipe.
+    """
+    import torch
+    rng = np.random.default_rng(w.seed)
+    gen = torch.Generator(device=device)
+    gen.manual_seed(w.seed)
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    out = {}
+    out["w_router"] = torch.from_numpy(rng.standard_normal((w.E, w.d_model), dtype=np.float32) * np.float32(0.02)).to(device)
+    b = router_bias(w, rng)
+    out["bias"] = None if b is None else torch.from_numpy(b).to(device)
+    out["x"] = torch.randn((w.T, w.d_model), generator=gen, device=device, dtype=torch.float32).to(tdt)
+    out["w1"] = out["w3"] = out["w2"] = None
+    if with_experts and w.d_ff > 0:
+        shapes = {"w1": (w.E, w.d_ff, w.d_model), "w3": (w.E, w.d_ff, w.d_model), "w2": (w.E, w.d_model, w.d_ff)}
+        for name, shp in shapes.items():
+            if name == "w3" and w.act != "swiglu":
+                continue
+            m = torch.empty(shp, device=device, dtype=tdt)
+            for e in range(w.E):  # per expert, to bound the fp32 temporary
+                m[e] = (torch.randn(shp[1:], generator=gen, device=device, dtype=torch.float32) * 0.02).to(tdt)
+            out[name] = m
     return out
 
 

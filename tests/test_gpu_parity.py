@@ -1,0 +1,219 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: integer tables bit-exact; combine weights |err| <= 1e-6; logits rel-L2 <= 1e-5 (fp32
+accumulation of a fp32 dot product against the float64 oracle rounded to fp32); layer output
+rel-L2 <= 1e-5 (fp32 workload) / <= 2e-2 (bf16 workloads).
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2402_12399_amd as rr
+from oracle import rectify_router as orc
+from paper_2402_12399_amd import workloads as wl
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+MODES = [(), ("ir",), ("fr",), ("ir", "fr")]
+
+
+def _oracle_tables(a, cfg, mode, arrival=False):
+    return orc.route(a, cfg.k, cfg.G, cfg.capacity_factor, "ir" in mode, "fr" in mode,
+                     orc.POLICY_ARRIVAL if arrival else orc.POLICY_SCORE)
+
+
+# ------------------------------------------------------------------ routing tables, identical logits
+DISPATCH_CASES = [
+    # T, E, G, k, cf, ties
+    (256, 8, 2, 1, 1.0, False),
+    (1000, 8, 4, 2, 1.25, False),     # ragged last token block
+    (1000, 6, 2, 2, 0.5, True),       # E not a power of two, many ties, +-0
+    (4099, 16, 1, 1, 1.0, True),      # prime T, one group
+    (3 * 128, 64, 8, 2, 0.75, False),
+    (5000, 64, 8, 4, 2.0, True),      # largest k, k+1 rounds
+    (130, 4, 2, 3, 3.0, False),       # k+1 == E
+    (64, 2, 2, 2, 1.0, True),         # k == E: no Fill-in possible
+    (20000, 32, 8, 1, 0.5, False),
+]
+
+
+@pytest.mark.parametrize("T,E,G,k,cf,ties", DISPATCH_CASES)
+@pytest.mark.parametrize("mode", MODES, ids=["vanilla", "ir", "fr", "ir+fr"])
+def test_dispatch_tables_bit_exact(T, E, G, k, cf, ties, mode):
+    if "fr" in mode and k + 1 > E:
+        pytest.skip("Fill-in needs k+1 <= E")
+    a = wl.synthetic_logits(T, E, seed=T + E + k, bias_std=1.0, ties=ties)
+    for arrival in (False, True):
+        cfg = rr.RRConfig(T, 64, 0, E, k, G, cf, rr.RR_F32, rr.RR_ACT_SWIGLU, gu.flags_of(mode, arrival))
+        got = gu.run_dispatch(cfg, a)
+        gu.assert_tables_equal(got, _oracle_tables(a, cfg, mode, arrival))
+
+
+def test_dispatch_extreme_cases():
+    # every token wants the same expert; capacity 1; capacity >= T; all scores equal
+    T, E = 700, 8
+    a = np.zeros((T, E), dtype=np.float32)
+    a[:, 3] = 5.0
+    for cf, k in [(1.0, 1), (0.001, 2), (float(E), 2)]:
+        cfg = rr.RRConfig(T, 64, 0, E, k, 2, cf, rr.RR_F32, rr.RR_ACT_SWIGLU, rr.RR_INTRA_GPU | rr.RR_FILL_IN)
+        gu.assert_tables_equal(gu.run_dispatch(cfg, a), _oracle_tables(a, cfg, ("ir", "fr")))
+    a[:] = 1.0
+    cfg = rr.RRConfig(T, 64, 0, E, 2, 4, 1.0, rr.RR_F32, rr.RR_ACT_SWIGLU, rr.RR_INTRA_GPU | rr.RR_FILL_IN)
+    gu.assert_tables_equal(gu.run_dispatch(cfg, a), _oracle_tables(a, cfg, ("ir", "fr")))
+    # a single token
+    a1 = wl.synthetic_logits(1, 4, seed=9)
+    cfg = rr.RRConfig(1, 64, 0, 4, 2, 1, 1.0, rr.RR_F32, rr.RR_ACT_SWIGLU, rr.RR_INTRA_GPU | rr.RR_FILL_IN)
+    gu.assert_tables_equal(gu.run_dispatch(cfg, a1), _oracle_tables(a1, cfg, ("ir", "fr")))
+
+
+def test_dispatch_deterministic():
+    a = wl.synthetic_logits(30000, 64, seed=77, ties=True)
+    cfg = rr.RRConfig(30000, 64, 0, 64, 2, 8, 0.75, rr.RR_F32, rr.RR_ACT_SWIGLU, rr.RR_INTRA_GPU | rr.RR_FILL_IN)
+    first = gu.run_dispatch(cfg, a)
+    for _ in range(3):
+        again = gu.run_dispatch(cfg, a)
+        for name in gu.INT_TABLES + ("combine_w",):
+            assert np.array_equal(first[name], again[name]), name
+
+
+# ------------------------------------------------------------------ router scores
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("T,d,E,k", [(256, 64, 8, 1), (1000, 264, 6, 2), (513, 1024, 64, 2), (2048, 2048, 16, 1)])
+def test_router_scores(dtype, T, d, E, k):
+    rng = np.random.default_rng(T + d)
+    x = wl._store(rng.standard_normal((T, d), dtype=np.float32), dtype)
+    wr = rng.standard_normal((E, d), dtype=np.float32) * np.float32(0.05)
+    b = rng.standard_normal(E).astype(np.float32)
+    cfg = rr.RRConfig(T, d, 0, E, k, 1, 1.0, rr.RR_F32 if dtype == "f32" else rr.RR_BF16)
+    logits = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    probs = torch.empty((T, E), dtype=torch.float32, device="cuda")
+    ranks = torch.empty((T, k + 1), dtype=torch.int32, device="cuda")
+    for bias in (b, None):
+        rr.rr_router_scores(cfg, gu.to_device(x, dtype), torch.from_numpy(wr).cuda(),
+                            None if bias is None else torch.from_numpy(bias).cuda(), logits, probs, ranks)
+        torch.cuda.synchronize()
+        want = orc.router_scores(wl.values_f32(x, dtype), wr, bias)
+        got = logits.cpu().numpy()
+        assert gu.rel_l2(got.astype(np.float64), want.astype(np.float64)) <= 1e-5
+        assert np.abs(got - want).max() <= 1e-5 * max(1.0, np.abs(want).max())
+        # d p = p (d a - sum p d a): at most twice the logit error, plus fp32 rounding of exp and the sum
+        assert np.abs(probs.cpu().numpy() - orc.softmax_probs(want)).max() <= 2e-5 * max(1.0, np.abs(want).max()) + 1e-6
+        # ranking: equal to the oracle's wherever the oracle's scores are not within rounding of a tie
+        want_rank = orc.rank_experts(want, k + 1)
+        got_rank = ranks.cpu().numpy()
+        srt = -np.sort(-want.astype(np.float64), axis=1)
+        clear = (srt[:, :k + 1] - srt[:, 1:k + 2]).min(axis=1) > 1e-4 if E > k + 1 else np.ones(T, bool)
+        assert np.array_equal(got_rank[clear], want_rank[clear])
+        assert clear.mean() > 0.99
+
+
+# ------------------------------------------------------------------ whole layer
+def _forward_case(w, mode, inputs, tol, sample=None, arrival=False):
+    cfg = gu.config_of(w, mode, arrival, T=inputs["x"].shape[0])
+    dev = {n: (torch.from_numpy(inputs[n]).cuda() if n in ("w_router", "bias") and inputs[n] is not None
+               else gu.to_device(inputs[n], w.dtype)) for n in ("x", "w_router", "bias", "w1", "w3", "w2")}
+    out, tables, logits = gu.run_forward(cfg, dev)
+    f32 = lambda n: None if inputs[n] is None else wl.values_f32(inputs[n], w.dtype)
+    a, want_tables, want_out = orc.moe_forward(
+        f32("x"), inputs["w_router"], inputs["bias"], f32("w1"), f32("w3"), f32("w2"), w.k, w.G,
+        w.capacity_factor, w.act, "ir" in mode, "fr" in mode,
+        orc.POLICY_ARRIVAL if arrival else orc.POLICY_SCORE, tokens=sample)
+    assert gu.rel_l2(logits.astype(np.float64), a.astype(np.float64)) <= 1e-5
+    gu.assert_tables_equal(tables, want_tables, cw_atol=2e-5)  # weights from logits that differ by rounding
+    got = gu.to_host_f64(out)
+    if sample is not None:
+        got = got[sample]
+    err = gu.rel_l2(got, want_out)
+    assert err <= tol, f"rel-L2 {err}"
+    unprocessed = np.flatnonzero(want_tables["combine_w"].sum(axis=1) == 0)
+    assert (gu.to_host_f64(out)[unprocessed] == 0).all()
+    return err
+
+
+@pytest.mark.parametrize("mode", MODES, ids=["vanilla", "ir", "fr", "ir+fr"])
+def test_forward_c1_fp32(mode):
+    _forward_case(wl.C1, mode, wl.make_inputs(wl.C1), 1e-5)
+
+
+def test_forward_c1_arrival_policy():
+    _forward_case(wl.C1, ("ir", "fr"), wl.make_inputs(wl.C1), 1e-5, arrival=True)
+
+
+SMALL_BF16 = [
+    wl.Workload("s1", 1024, 256, 512, 8, 2, 2, 1.25, "bf16", "swiglu", "normal:0.5", 11),
+    wl.Workload("s2", 1000, 136, 264, 6, 2, 1, 0.5, "bf16", "swiglu", "zipf:1.5", 12),   # ragged everything
+    wl.Workload("s3", 768, 128, 256, 4, 4, 1, 1.0, "bf16", "gelu", "normal:1.0", 13),
+    wl.Workload("s4", 600, 72, 200, 4, 2, 2, 1.0, "f32", "swiglu", "normal:1.0", 14),
+]
+
+
+@pytest.mark.parametrize("w", SMALL_BF16, ids=[w.name for w in SMALL_BF16])
+@pytest.mark.parametrize("mode", [(), ("ir", "fr")], ids=["vanilla", "ir+fr"])
+def test_forward_small(w, mode):
+    _forward_case(w, mode, wl.make_inputs(w), 1e-5 if w.dtype == "f32" else 2e-2)
+
+
+def _full_size_case(w, mode, n_sample=1024):
+    """Full-size workload in the configuration the benchmark times; oracle outputs on a token sample."""
+    dev = wl.make_inputs_device(w)
+    cfg = gu.config_of(w, mode)
+    out, tables, logits = gu.run_forward(cfg, dev)
+    x = wl.values_f32(gu.to_host_storage(dev["x"]), w.dtype)
+    wr, b = dev["w_router"].cpu().numpy(), None if dev["bias"] is None else dev["bias"].cpu().numpy()
+    a = orc.router_scores(x, wr, b)
+    assert gu.rel_l2(logits.astype(np.float64), a.astype(np.float64)) <= 1e-5
+    want = orc.route(a, w.k, w.G, w.capacity_factor, "ir" in mode, "fr" in mode)
+    gu.assert_tables_equal(tables, want, cw_atol=2e-5)
+    sample = np.sort(np.random.default_rng(w.seed).choice(w.T, n_sample, replace=False))
+
+    class PerExpert:  # expert weights are pulled to the host one expert at a time
+        def __init__(self, t):
+            self.t, self.shape = t, t.shape
+
+        def __getitem__(self, j):
+            return wl.values_f32(gu.to_host_storage(self.t[j]), w.dtype)
+
+    want_out = orc.moe_output(x, want, w.k, PerExpert(dev["w1"]), PerExpert(dev["w3"]), PerExpert(dev["w2"]),
+                              w.act, tokens=sample)
+    got = gu.to_host_f64(out[torch.from_numpy(sample).cuda()])
+    err = gu.rel_l2(got, want_out)
+    assert err <= 2e-2, f"rel-L2 {err}"
+    # per-token errors are bounded too (a mis-routed token would show as a row error of order 1)
+    row_err = np.linalg.norm(got - want_out, axis=1) / np.maximum(np.linalg.norm(want_out, axis=1), 1e-6)
+    assert row_err.max() <= 0.1
+    return tables
+
+
+@pytest.mark.parametrize("mode", MODES, ids=["vanilla", "ir", "fr", "ir+fr"])
+def test_forward_c2_full_size(mode):
+    _full_size_case(wl.C2, mode)
+
+
+def test_forward_c3_full_size():
+    _full_size_case(wl.C3, ("ir", "fr"), n_sample=512)
+
+
+def test_forward_c5_full_size():
+    t = _full_size_case(wl.C5, ("ir", "fr"), n_sample=512)
+    # the workload is meant to overflow heavily and leave experts vacant
+    assert (t["slot"][:, 0] < 0).mean() > 0.30
+    assert (t["fill_topk"] < wl.C5.T * 0.5 / wl.C5.E).sum() >= 4
+
+
+def test_c4_routing_full_size():
+    """1M tokens, 64 experts, top-2: logits on sampled rows, tables bit-exact from identical logits."""
+    w = wl.C4
+    dev = wl.make_inputs_device(w, with_experts=False)
+    cfg = gu.config_of(w)
+    logits = torch.empty((w.T, w.E), dtype=torch.float32, device="cuda")
+    rr.rr_router_scores(cfg, dev["x"], dev["w_router"], None, logits)
+    torch.cuda.synchronize()
+    sample = np.sort(np.random.default_rng(4).choice(w.T, 4096, replace=False))
+    want = orc.router_scores(dev["x"][torch.from_numpy(sample).cuda()].cpu().numpy(), dev["w_router"].cpu().numpy())
+    got = logits[torch.from_numpy(sample).cuda()].cpu().numpy()
+    assert gu.rel_l2(got.astype(np.float64), want.astype(np.float64)) <= 1e-5
+    # routing tables: the oracle and the HIP path are given the same fp32 logits (drawn on the host)
+    a = wl.synthetic_logits(w.T, w.E, seed=4, bias_std=0.0)
+    a *= np.float32(0.64)  # std of w.x at d_model 1024 with N(0, 0.02) router weights
+    gu.assert_tables_equal(gu.run_dispatch(cfg, a), orc.route(a, w.k, w.G, w.capacity_factor, True, True))
