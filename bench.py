@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the Rectify-Router MoE-layer forward on one MI355X.
+
+A step is one rr_moe_forward call (router -> capacity slotting -> Intra-GPU and Fill-in
+rectification -> dispatch gather -> expert FFN grouped GEMM -> weighted combine) over one
+synthetic batch that is already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c1] [--mode ir+fr]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (see profiles/); None until measured for the workload.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--mode", default="ir+fr", help="vanilla | ir | fr | ir+fr")
+    ap.add_argument("--cpu-sample", type=int, default=2048, help="tokens the CPU oracle computes outputs for (0 = skip)")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the expert-parallel groups are simulated in HBM); "
+              "--gpus must be 1", file=sys.stderr)
+        return 2
+    import torch
+    import paper_2402_12399_amd as rr
+    from paper_2402_12399_amd import workloads as wl
+
+    w = wl.ALL[args.workload]
+    if w.d_ff == 0:
+        print("bench.py: workload has no expert FFN; use a forward workload", file=sys.stderr)
+        return 2
+    mode = () if args.mode == "vanilla" else tuple(args.mode.split("+"))
+    flags = (rr.RR_INTRA_GPU if "ir" in mode else 0) | (rr.RR_FILL_IN if "fr" in mode else 0)
+    cfg = rr.RRConfig(w.T, w.d_model, w.d_ff, w.E, w.k, w.G, w.capacity_factor,
+                      rr.RR_F32 if w.dtype == "f32" else rr.RR_BF16,
+                      rr.RR_ACT_GELU if w.act == "gelu" else rr.RR_ACT_SWIGLU, flags)
+    torch.cuda.set_device(0)
+    dev = wl.make_inputs_device(w)
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    out = torch.empty((w.T, w.d_model), dtype=tdt, device="cuda")
+    tables = rr.alloc_tables(cfg)
+    logits = torch.empty((w.T, w.E), dtype=torch.float32, device="cuda")
+    ws = rr.alloc_workspace(cfg)
+
+    def step():
+        rr.rr_moe_forward(cfg, dev["x"], dev["w_router"], dev["bias"], dev["w1"], dev["w3"], dev["w2"], out,
+                          tables, logits, ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-kernel durations: the same K steps again with every launch bracketed by HIP events on
+    # the launch stream
+    rr.rr_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    prof = rr.rr_profile_read()
+    ms_per_step_profiled = (time.perf_counter() - t0) * 1e3 / args.steps
+    rr.rr_profile_enable(False)
+    kernels = {n: ms / max(c, 1) for n, (c, ms) in prof.items() if c > 0}
+
+    th = tables.to_host()
+    C = tables.capacity
+    slot_rows = int(th["fill_total"].sum())
+    ir_rows = int(th["ir_offset"][-1])
+    R = slot_rows + ir_rows
+    es = 4 if w.dtype == "f32" else 2
+    gated = w.act == "swiglu"
+    flops = {"ffn_gate_up": (4 if gated else 2) * w.d_model * w.d_ff * R, "ffn_down": 2 * w.d_model * w.d_ff * R}
+    dom = max(kernels, key=kernels.get)
+    peak_tf = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
+    if dom in flops:
+        achieved = flops[dom] / (kernels[dom] * 1e-3) / 1e12
+        roofline = {"kernel": dom, "bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": achieved,
+                    "peak": peak_tf, "unit": "TFLOP/s", "frac": achieved / peak_tf,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
+                    "flops_per_launch": flops[dom], "avg_ms": kernels[dom]}
+    else:
+        roofline = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                    "frac": None, "traffic": None, "avg_ms": kernels[dom]}
+    ffn_ms = kernels.get("ffn_gate_up", 0) + kernels.get("ffn_down", 0)
+    ffn_tf = (flops["ffn_gate_up"] + flops["ffn_down"]) / (ffn_ms * 1e-3) / 1e12 if ffn_ms else None
+    routing_names = ("router_scores", "topk_rank", "scan_candidates", "plan_rounds", "scatter_candidates",
+                     "select_slot", "ir_count", "ir_scan", "row_plan", "ir_weights")
+    routing_ms = sum(kernels.get(n, 0.0) for n in routing_names)
+
+    cpu = None
+    if args.cpu_sample > 0:
+        cpu = cpu_baseline(w, mode, dev, min(args.cpu_sample, w.T))
+
+    line = {
+        "metric": "rectified_moe_layer_tokens_per_s", "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": w.name, "mode": "top%d" % w.k + "".join("+" + m for m in mode), "T": w.T,
+                   "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k, "G": w.G,
+                   "capacity_factor": w.capacity_factor, "capacity": C, "act": w.act, "router": "fp32",
+                   "parallelism": "1 GPU, %d simulated expert-parallel groups" % w.G},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "ms_per_step_with_events": ms_per_step_profiled,
+        "kernel_ms": {n: round(v, 5) for n, v in kernels.items()},
+        "ffn_tflops": ffn_tf,
+        "routing_rectify_mtokens_per_s": w.T / (routing_ms * 1e-3) / 1e6 if routing_ms else None,
+        "rows": {"slot_rows": slot_rows, "ir_rows": ir_rows, "capacity_slots": w.E * C,
+                 "dropped_assignments": int((th["slot"][:, :w.k] < 0).sum()),
+                 "fill_in_placed": int((th["slot"][:, w.k] >= 0).sum()), "padding_slots": w.E * C - slot_rows},
+    }
+    print(json.dumps(line))
+    return 0
+
+
+def cpu_baseline(w, mode, dev, n_sample):
+    """The CPU oracle as it stands, timed on this host: routing of the full batch plus expert
+    outputs for the first n_sample tokens, scaled to tokens/s of the whole layer."""
+    from oracle import rectify_router as orc
+    from paper_2402_12399_amd import workloads as wl
+    import torch
+
+    def host(t):
+        if t is None:
+            return None
+        if t.dtype == torch.bfloat16:
+            return wl.bf16_bits_to_f32(t.view(torch.int16).cpu().numpy().view(np.uint16))
+        return t.cpu().numpy()
+
+    h = {n: host(dev[n]) for n in ("x", "w_router", "bias", "w1", "w3", "w2")}
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = int(os.environ.get("OMP_NUM_THREADS", "1"))
+    t0 = time.perf_counter()
+    a = orc.router_scores(h["x"], h["w_router"], h["bias"])
+    tb = orc.route(a, w.k, w.G, w.capacity_factor, "ir" in mode, "fr" in mode)
+    t_route = time.perf_counter() - t0
+    sample = np.arange(n_sample)
+    t0 = time.perf_counter()
+    orc.moe_output(h["x"], tb, w.k, h["w1"], h["w3"], h["w2"], w.act, tokens=sample)
+    t_ffn = time.perf_counter() - t0
+    total = t_route + t_ffn * (w.T / n_sample)
+    return {"value": w.T / total, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "routing of all %d tokens (%.2f s) + float64 expert outputs of the first %d tokens (%.2f s), "
+                      "FFN time scaled by %d/%d" % (w.T, t_route, n_sample, t_ffn, w.T, n_sample)}
+
+
+if __name__ == "__main__":
+    sys.exit(main())
