@@ -46,14 +46,48 @@ struct GemmArgs {
 // WAVES_M x WAVES_N waves, each owning WM x WN fragments of 32x32.
 // GATED: the staged B rows are [BN gate rows | BN up rows] with BN = BROWS / 2, and a wave's
 // fragments j < WN/2 are gate columns, j >= WN/2 the matching up columns.
-template <int WAVES_M, int WAVES_N, int WM, int WN, bool GATED, int ACT>
-__global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(GemmArgs P) {
-  static_assert(WAVES_M * WAVES_N == 4, "four waves");
+// Epilogue shared by the bf16 kernels: activation, round to bf16, store (masked on edge tiles).
+// Accumulator element v of a 32x32 fragment is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32.
+template <int WAVES_N, int WM, int WN, bool GATED, int ACT>
+__device__ inline void store_tile(f32x16 (&acc)[WM][WN], uint16_t *Cb, int rbase, int rows_e, int m0, int n0, int N,
+                                  int wm, int wn, int lane) {
+  constexpr int NJ = GATED ? WN / 2 : WN;           // output column fragments per wave
+  constexpr int BM = 0;                             // (unused; tile extents come from the wave layout)
+  (void)BM;
+  const int fr = lane & 31, fh = lane >> 5;
+  const int wrow0 = m0 + wm * WM * 32, wcol0 = n0 + wn * NJ * 32;
+  const bool interior = wrow0 + WM * 32 <= rows_e && wcol0 + NJ * 32 <= N;
+  uint16_t *base = Cb + (size_t)(rbase + wrow0 + 4 * fh) * N + wcol0 + fr;
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      uint16_t *p = base + (size_t)(i * 32) * N + j * 32;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        float c = acc[i][j][v];
+        if (GATED) c = silu(c) * acc[i][j + NJ][v];
+        if (ACT == RR_ACT_GELU) c = gelu_erf(c);
+        const int dr = 8 * (v >> 2) + (v & 3);
+        if (interior || (wrow0 + i * 32 + 4 * fh + dr < rows_e && wcol0 + j * 32 + fr < N))
+          p[(size_t)dr * N] = (uint16_t)f32_to_bf16_bits(c);
+      }
+    }
+  }
+}
+
+template <int SWZ>
+__device__ inline int swz(int r) { return SWZ == 0 ? (r & 7) : ((r >> 1) & 7); }
+
+template <int WAVES_M, int WAVES_N, int WM, int WN, bool GATED, int ACT, int SWZ>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_kernel(GemmArgs P) {
+  constexpr int NTHR = WAVES_M * WAVES_N * 64;
+  constexpr int RPP = NTHR / 8;       // rows covered by one pass of 16-byte loads
   constexpr int BM = WAVES_M * WM * 32;
   constexpr int BROWS = WAVES_N * WN * 32;
   constexpr int BN = GATED ? BROWS / 2 : BROWS;
-  constexpr int A_LD = BM / 32;       // 16-byte loads per thread per chunk
-  constexpr int B_LD = BROWS / 32;
+  constexpr int A_LD = BM / RPP;      // 16-byte loads per thread per chunk
+  constexpr int B_LD = BROWS / RPP;
   constexpr int STAGE_BYTES = (BM + BROWS) * GB_ROW_BYTES;
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -79,20 +113,20 @@ __global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(GemmArgs P) {
   int lds_off_a[A_LD], lds_off_b[B_LD];
 #pragma unroll
   for (int i = 0; i < A_LD; ++i) {
-    int r = (tid >> 3) + 32 * i;
+    int r = (tid >> 3) + RPP * i;
     int gr = min(m0 + r, rows_e - 1);
     a_src[i] = Ab + ((size_t)(rbase + gr) * K + lc * 8) * 2;
-    lds_off_a[i] = r * GB_ROW_BYTES + ((lc ^ (r & 7)) << 4);
+    lds_off_a[i] = r * GB_ROW_BYTES + ((lc ^ swz<SWZ>(r)) << 4);
   }
 #pragma unroll
   for (int i = 0; i < B_LD; ++i) {
-    int r = (tid >> 3) + 32 * i;
+    int r = (tid >> 3) + RPP * i;
     const char *bb = B0b;
     int nr = r;
     if (GATED && r >= BN) { bb = B1b; nr = r - BN; }
     int gn = min(n0 + nr, N - 1);
     b_src[i] = bb + ((size_t)gn * K + lc * 8) * 2;
-    lds_off_b[i] = BM * GB_ROW_BYTES + r * GB_ROW_BYTES + ((lc ^ (r & 7)) << 4);
+    lds_off_b[i] = BM * GB_ROW_BYTES + r * GB_ROW_BYTES + ((lc ^ swz<SWZ>(r)) << 4);
   }
 
   f32x16 acc[WM][WN];
@@ -128,7 +162,7 @@ __global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(GemmArgs P) {
   for (int i = 0; i < WM; ++i) {
     int r = (wm * WM + i) * 32 + fr;
     a_row_off[i] = r * GB_ROW_BYTES;
-    a_sw[i] = r & 7;
+    a_sw[i] = swz<SWZ>(r);
   }
 #pragma unroll
   for (int j = 0; j < WN; ++j) {
@@ -140,7 +174,7 @@ __global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(GemmArgs P) {
       r = (wn * WN + j) * 32 + fr;
     }
     b_row_off[j] = BM * GB_ROW_BYTES + r * GB_ROW_BYTES;
-    b_sw[j] = r & 7;
+    b_sw[j] = swz<SWZ>(r);
   }
 
   load_global(0);
@@ -166,41 +200,156 @@ __global__ __launch_bounds__(GB_THREADS) void gemm_bf16_kernel(GemmArgs P) {
     __syncthreads();
   }
 
-  // epilogue: accumulator element v of a 32x32 fragment is row 8*(v/4) + 4*(lane/32) + v%4, column lane%32
-  uint16_t *Cb = static_cast<uint16_t *>(P.Cout);
+  store_tile<WAVES_N, WM, WN, GATED, ACT>(acc, static_cast<uint16_t *>(P.Cout), rbase, rows_e, m0, n0, N, wm, wn, lane);
+}
+
+// Direct-to-LDS variant (K % 64 == 0): global_load_lds_dwordx4 moves 16 bytes per lane straight
+// into LDS, a wave instruction filling 1 KB = 8 consecutive LDS rows (lane l -> row l/8, chunk
+// position l%8), so the swizzle is applied on the global side: the lane fetches the chunk that
+// belongs at its position.  Two 64 KB stages; the loads of chunk kt+1 are in flight during all
+// MFMAs of chunk kt, and fragments are double-buffered in registers across the four 16-wide
+// k-steps of a chunk.
+template <int WAVES_M, int WAVES_N, int WM, int WN, bool GATED, int ACT, int SWZ>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void gemm_bf16_dl_kernel(GemmArgs P) {
+#if defined(__HIP_DEVICE_COMPILE__)  // buffer-resource and LDS-DMA builtins exist in the device pass only
+  constexpr int NW = WAVES_M * WAVES_N;
+  constexpr int BM = WAVES_M * WM * 32;
+  constexpr int BROWS = WAVES_N * WN * 32;
+  constexpr int BN = GATED ? BROWS / 2 : BROWS;
+  constexpr int STAGE_BYTES = (BM + BROWS) * GB_ROW_BYTES;
+  constexpr int NI = (BM + BROWS) / 8 / NW;  // load instructions per wave per chunk
+  constexpr int NIA = BM / 8 / NW, NIB0 = BN / 8 / NW;
+  static_assert(BM % (8 * NW) == 0 && BN % (8 * NW) == 0, "operand boundaries must fall between load instructions");
+  extern __shared__ __attribute__((aligned(16))) char smem[];
+
+  const int mt = blockIdx.x / P.NT;
+  if (mt >= *P.n_tiles) return;
+  const int e = P.tile_expert[mt];
+  const int m0 = P.tile_row0[mt];
+  const int rbase = P.row_base[e];
+  const int rows_e = P.row_base[e + 1] - rbase;
+  const int n0 = (blockIdx.x - mt * P.NT) * BN;
+  const int K = P.K, N = P.N;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int wm = w / WAVES_N, wn = w % WAVES_N;
+
+  const char *Ab = static_cast<const char *>(P.A);
+  const char *B0b = static_cast<const char *>(P.B0) + (size_t)e * N * K * 2;
+  const char *B1b = GATED ? static_cast<const char *>(P.B1) + (size_t)e * N * K * 2 : nullptr;
+
+  // instruction i of wave w fills stage rows [8 q, 8 q + 8), q = i * NW + w.  Buffer loads: one
+  // descriptor per operand, rows past the end of the operand read as zero.
+  const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char *>(Ab + (size_t)rbase * K * 2), 0, (int)min((size_t)rows_e * K * 2, (size_t)0x7fffffff), 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsB0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(B0b), 0, N * K * 2, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rsB1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(GATED ? B1b : B0b), 0, N * K * 2, 0x00020000);
+  int voff[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int r = (i * NW + w) * 8 + (lane >> 3);
+    const int c = (lane & 7) ^ swz<SWZ>(r);
+    int row;
+    if (r < BM) {
+      row = m0 + r;
+    } else {
+      int nr = r - BM;
+      if (GATED && nr >= BN) nr -= BN;
+      row = n0 + nr;
+    }
+    voff[i] = row * K * 2 + c * 16;
+  }
+  auto issue_loads = [&](int kt, int buf) {
+    char *st = smem + buf * STAGE_BYTES + w * 1024;
+    const int koff = kt * (GB_BK * 2);
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
+      // which operand instruction i reads is known at compile time: 8 NW | BM and 8 NW | BN
+      auto lp = (__attribute__((address_space(3))) void *)(st + i * NW * 1024);
+      if (i < NIA)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, lp, 16, voff[i], koff, 0, 0);
+      else if (!GATED || i < NIA + NIB0)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB0, lp, 16, voff[i], koff, 0, 0);
+      else
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB1, lp, 16, voff[i], koff, 0, 0);
+    }
+  };
+
+  const int fr = lane & 31, fh = lane >> 5;
+  int a_off[WM], b_off[WN], a_sw[WM], b_sw[WN];
 #pragma unroll
   for (int i = 0; i < WM; ++i) {
-    const int frag_row0 = m0 + (wm * WM + i) * 32 + 4 * fh;
+    int r = (wm * WM + i) * 32 + fr;
+    a_off[i] = r * GB_ROW_BYTES;
+    a_sw[i] = swz<SWZ>(r);
+  }
+#pragma unroll
+  for (int j = 0; j < WN; ++j) {
+    int r;
     if (GATED) {
       constexpr int H = WN / 2;
-#pragma unroll
-      for (int j = 0; j < H; ++j) {
-        const int col = n0 + (wn * H + j) * 32 + fr;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = frag_row0 + 8 * (v >> 2) + (v & 3);
-          if (row < rows_e && col < N) {
-            float g = acc[i][j][v], u = acc[i][j + H][v];
-            Cb[(size_t)(rbase + row) * N + col] = (uint16_t)f32_to_bf16_bits(silu(g) * u);
-          }
-        }
-      }
+      r = (j < H) ? (wn * H + j) * 32 + fr : BN + (wn * H + (j - H)) * 32 + fr;
     } else {
-#pragma unroll
-      for (int j = 0; j < WN; ++j) {
-        const int col = n0 + (wn * WN + j) * 32 + fr;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = frag_row0 + 8 * (v >> 2) + (v & 3);
-          if (row < rows_e && col < N) {
-            float c = acc[i][j][v];
-            if (ACT == RR_ACT_GELU) c = gelu_erf(c);
-            Cb[(size_t)(rbase + row) * N + col] = (uint16_t)f32_to_bf16_bits(c);
-          }
-        }
-      }
+      r = (wn * WN + j) * 32 + fr;
     }
+    b_off[j] = (BM + r) * GB_ROW_BYTES;
+    b_sw[j] = swz<SWZ>(BM + r);
   }
+
+  f32x16 acc[WM][WN];
+#pragma unroll
+  for (int i = 0; i < WM; ++i)
+#pragma unroll
+    for (int j = 0; j < WN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  const int KT = K / GB_BK;
+  bf16x8 af[2][WM], bfr[2][WN];
+  auto load_frags = [&](const char *st, int ks, int slot) {
+    const int c = 2 * ks + fh;
+#pragma unroll
+    for (int i = 0; i < WM; ++i) af[slot][i] = *reinterpret_cast<const bf16x8 *>(st + a_off[i] + ((c ^ a_sw[i]) << 4));
+#pragma unroll
+    for (int j = 0; j < WN; ++j) bfr[slot][j] = *reinterpret_cast<const bf16x8 *>(st + b_off[j] + ((c ^ b_sw[j]) << 4));
+  };
+  auto mfma_step = [&](int slot) {
+#pragma unroll
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+  };
+  // Software pipeline.  sched_barrier(0) pins the order "fragment loads of the NEXT k-step, then the
+  // MFMAs of the current one", so every LDS read has a whole MFMA block to complete in.  The last
+  // k-step of a chunk runs after the barrier, overlapping the first fragment loads of the next
+  // chunk and the issue of the global loads two chunks ahead.  The loop is rotated so that its
+  // body starts at the barrier.
+  auto step = [&](const char *st, int ks_next, int slot_next, int slot_now) {
+    load_frags(st, ks_next, slot_next);
+    __builtin_amdgcn_sched_barrier(0);
+    mfma_step(slot_now);
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  issue_loads(0, 0);
+  __syncthreads();  // waits for this wave's loads (vmcnt 0), then for everybody's
+  if (KT > 1) issue_loads(1, 1);
+  load_frags(smem, 0, 0);
+  step(smem, 1, 1, 0);
+  step(smem, 2, 0, 1);
+  step(smem, 3, 1, 0);
+  for (int kt = 1; kt < KT; ++kt) {
+    // chunk kt has landed (mine: vmcnt 0; everybody's: barrier) and nobody reads the other stage any more
+    __syncthreads();
+    if (kt + 1 < KT) issue_loads(kt + 1, (kt + 1) & 1);
+    const char *st = smem + (kt & 1) * STAGE_BYTES;
+    step(st, 0, 0, 1);  // MFMAs: last k-step of chunk kt-1
+    step(st, 1, 1, 0);
+    step(st, 2, 0, 1);
+    step(st, 3, 1, 0);
+  }
+  mfma_step(1);
+  store_tile<WAVES_N, WM, WN, GATED, ACT>(acc, static_cast<uint16_t *>(P.Cout), rbase, rows_e, m0, n0, N, wm, wn, lane);
+#endif
 }
 
 // ------------------------------------------------------------------ fp32 path
@@ -285,48 +434,78 @@ hipError_t set_lds(Kern kern, int bytes) {
 
 }  // namespace
 
-hipError_t launch_ffn(const Dims &D, const void *w1, const void *w3, const void *w2, const Work &W, hipStream_t s) {
+// Tile configuration: 2 x 4 waves, each 4 x 2 fragments of 32x32 -> 256 x 256 staged rows, two waves
+// per SIMD so that one wave's LDS reads overlap the other's MFMAs.
+#ifndef RR_GEMM_CFG
+#define RR_GEMM_CFG 2, 4, 4, 2
+#define RR_GEMM_THREADS 512
+#define RR_GEMM_SWZ 1
+#endif
+
+// which: bit 0 = up projection (+ activation), bit 1 = down projection
+hipError_t launch_ffn_part(const Dims &D, const void *w1, const void *w3, const void *w2, const Work &W,
+                           hipStream_t s, int which) {
   GemmArgs up{W.x_disp, w1, w3, W.h, D.d, D.F, 0, W.row_base, W.tile_expert, W.tile_row0, W.n_tiles};
   GemmArgs down{W.h, w2, nullptr, W.y, D.F, D.d, 0, W.row_base, W.tile_expert, W.tile_row0, W.n_tiles};
   hipError_t err = hipSuccess;
   if (D.dtype == RR_BF16) {
     // 256 x 256 staged rows; BM must equal Dims::BM (row tiles are cut by row_plan)
     constexpr int LDS = 2 * (256 + 256) * GB_ROW_BYTES;
-    auto k_up_gated = gemm_bf16_kernel<2, 2, 4, 4, true, -1>;
-    auto k_up_gelu = gemm_bf16_kernel<2, 2, 4, 4, false, RR_ACT_GELU>;
-    auto k_down = gemm_bf16_kernel<2, 2, 4, 4, false, -1>;
+    // direct-to-LDS kernels need whole 64-element K chunks; other sizes take the register-staged kernels
+    const bool dl_up = D.d % GB_BK == 0, dl_dn = D.F % GB_BK == 0;
+    auto k_up_gated = dl_up ? gemm_bf16_dl_kernel<RR_GEMM_CFG, true, -1, RR_GEMM_SWZ>
+                            : gemm_bf16_kernel<RR_GEMM_CFG, true, -1, RR_GEMM_SWZ>;
+    auto k_up_gelu = dl_up ? gemm_bf16_dl_kernel<RR_GEMM_CFG, false, RR_ACT_GELU, RR_GEMM_SWZ>
+                           : gemm_bf16_kernel<RR_GEMM_CFG, false, RR_ACT_GELU, RR_GEMM_SWZ>;
+    auto k_down = dl_dn ? gemm_bf16_dl_kernel<RR_GEMM_CFG, false, -1, RR_GEMM_SWZ>
+                        : gemm_bf16_kernel<RR_GEMM_CFG, false, -1, RR_GEMM_SWZ>;
     static bool attr_done = false;
     if (!attr_done) {
-      if ((err = set_lds(k_up_gated, LDS)) != hipSuccess) return err;
-      if ((err = set_lds(k_up_gelu, LDS)) != hipSuccess) return err;
-      if ((err = set_lds(k_down, LDS)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_dl_kernel<RR_GEMM_CFG, true, -1, RR_GEMM_SWZ>, LDS)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_dl_kernel<RR_GEMM_CFG, false, RR_ACT_GELU, RR_GEMM_SWZ>, LDS)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_dl_kernel<RR_GEMM_CFG, false, -1, RR_GEMM_SWZ>, LDS)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_kernel<RR_GEMM_CFG, true, -1, RR_GEMM_SWZ>, LDS)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_kernel<RR_GEMM_CFG, false, RR_ACT_GELU, RR_GEMM_SWZ>, LDS)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_kernel<RR_GEMM_CFG, false, -1, RR_GEMM_SWZ>, LDS)) != hipSuccess) return err;
       attr_done = true;
     }
     up.NT = D.act == RR_ACT_SWIGLU ? (D.F + 127) / 128 : (D.F + 255) / 256;
     down.NT = (D.d + 255) / 256;
-    prof_begin(K_FFN_UP, s);
-    if (D.act == RR_ACT_SWIGLU)
-      k_up_gated<<<up.NT * D.max_mtiles, GB_THREADS, LDS, s>>>(up);
-    else
-      k_up_gelu<<<up.NT * D.max_mtiles, GB_THREADS, LDS, s>>>(up);
-    prof_end(K_FFN_UP, s);
-    prof_begin(K_FFN_DOWN, s);
-    k_down<<<down.NT * D.max_mtiles, GB_THREADS, LDS, s>>>(down);
-    prof_end(K_FFN_DOWN, s);
+    if (which & 1) {
+      prof_begin(K_FFN_UP, s);
+      if (D.act == RR_ACT_SWIGLU)
+        k_up_gated<<<up.NT * D.max_mtiles, RR_GEMM_THREADS, LDS, s>>>(up);
+      else
+        k_up_gelu<<<up.NT * D.max_mtiles, RR_GEMM_THREADS, LDS, s>>>(up);
+      prof_end(K_FFN_UP, s);
+    }
+    if (which & 2) {
+      prof_begin(K_FFN_DOWN, s);
+      k_down<<<down.NT * D.max_mtiles, RR_GEMM_THREADS, LDS, s>>>(down);
+      prof_end(K_FFN_DOWN, s);
+    }
   } else {
     up.NT = (D.F + GF_BN - 1) / GF_BN;
     down.NT = (D.d + GF_BN - 1) / GF_BN;
-    prof_begin(K_FFN_UP, s);
-    if (D.act == RR_ACT_SWIGLU)
-      gemm_f32_kernel<RR_ACT_SWIGLU><<<up.NT * D.max_mtiles, 256, 0, s>>>(up);
-    else
-      gemm_f32_kernel<RR_ACT_GELU><<<up.NT * D.max_mtiles, 256, 0, s>>>(up);
-    prof_end(K_FFN_UP, s);
-    prof_begin(K_FFN_DOWN, s);
-    gemm_f32_kernel<-1><<<down.NT * D.max_mtiles, 256, 0, s>>>(down);
-    prof_end(K_FFN_DOWN, s);
+    if (which & 1) {
+      prof_begin(K_FFN_UP, s);
+      if (D.act == RR_ACT_SWIGLU)
+        gemm_f32_kernel<RR_ACT_SWIGLU><<<up.NT * D.max_mtiles, 256, 0, s>>>(up);
+      else
+        gemm_f32_kernel<RR_ACT_GELU><<<up.NT * D.max_mtiles, 256, 0, s>>>(up);
+      prof_end(K_FFN_UP, s);
+    }
+    if (which & 2) {
+      prof_begin(K_FFN_DOWN, s);
+      gemm_f32_kernel<-1><<<down.NT * D.max_mtiles, 256, 0, s>>>(down);
+      prof_end(K_FFN_DOWN, s);
+    }
   }
   return hipGetLastError();
+}
+
+hipError_t launch_ffn(const Dims &D, const void *w1, const void *w3, const void *w2, const Work &W, hipStream_t s) {
+  return launch_ffn_part(D, w1, w3, w2, W, s, 3);
 }
 
 }  // namespace rr
