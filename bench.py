@@ -21,9 +21,13 @@ PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_FP32_TFLOPS = 157.3    # MI355X fp32 vector
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (see profiles/); None until measured for the workload.
-MEASURED_TRAFFIC_BYTES = {}
+# Bytes per launch that left the L2s (FETCH_SIZE x 2.0, the factor a 1 GiB copy reads) plus bytes
+# written (WRITE_SIZE x 1.0), from two rocprofv3 --pmc runs of this benchmark; see
+# profiles/bench_c2_forward_hbm_traffic.md.  Keyed by (workload, kernel); None where not measured.
+MEASURED_TRAFFIC_BYTES = {
+    ("c2_top1_bf16_zipf1.1", "ffn_gate_up"): 2432.5e6 + 114.7e6,
+    ("c2_top1_bf16_zipf1.1", "ffn_down"): 733.1e6 + 42.8e6,
+}
 
 
 def parse():
@@ -34,6 +38,11 @@ def parse():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--mode", default="ir+fr", help="vanilla | ir | fr | ir+fr")
     ap.add_argument("--cpu-sample", type=int, default=2048, help="tokens the CPU oracle computes outputs for (0 = skip)")
+    ap.add_argument("--no-routing-stress", action="store_true",
+                    help="skip the extra routing-only measurement (1M tokens, 64 experts, top-2)")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size kernel to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters by)")
     return ap.parse_args()
 
 
@@ -113,6 +122,14 @@ def main():
                      "select_slot", "ir_count", "ir_scan", "row_plan", "ir_weights")
     routing_ms = sum(kernels.get(n, 0.0) for n in routing_names)
 
+    stress = None if args.no_routing_stress else routing_stress(rr, wl, torch, args.steps, args.warmup)
+    if args.copy_probe:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     cpu = None
     if args.cpu_sample > 0:
         cpu = cpu_baseline(w, mode, dev, min(args.cpu_sample, w.T))
@@ -132,12 +149,51 @@ def main():
         "kernel_ms": {n: round(v, 5) for n, v in kernels.items()},
         "ffn_tflops": ffn_tf,
         "routing_rectify_mtokens_per_s": w.T / (routing_ms * 1e-3) / 1e6 if routing_ms else None,
+        "routing_stress": stress,
         "rows": {"slot_rows": slot_rows, "ir_rows": ir_rows, "capacity_slots": w.E * C,
                  "dropped_assignments": int((th["slot"][:, :w.k] < 0).sum()),
                  "fill_in_placed": int((th["slot"][:, w.k] >= 0).sum()), "padding_slots": w.E * C - slot_rows},
     }
     print(json.dumps(line))
     return 0
+
+
+def routing_stress(rr, wl, torch, steps, warmup):
+    """Routing-only workload (1M fp32 tokens, 64 experts in 8 groups, top-2, capacity factor 0.75):
+    rr_router_scores + rr_rectified_dispatch, the memory-bound part of the path."""
+    w = wl.C4
+    cfg = rr.RRConfig(w.T, w.d_model, 0, w.E, w.k, w.G, w.capacity_factor, rr.RR_F32, rr.RR_ACT_SWIGLU,
+                      rr.RR_INTRA_GPU | rr.RR_FILL_IN)
+    dev = wl.make_inputs_device(w, with_experts=False)
+    logits = torch.empty((w.T, w.E), dtype=torch.float32, device="cuda")
+    tables = rr.alloc_tables(cfg)
+    ws = rr.alloc_workspace(cfg)
+
+    def step():
+        rr.rr_router_scores(cfg, dev["x"], dev["w_router"], dev["bias"], logits)
+        rr.rr_rectified_dispatch(cfg, logits, tables, ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    rr.rr_profile_enable(True)
+    for _ in range(steps):
+        step()
+    prof = rr.rr_profile_read()
+    rr.rr_profile_enable(False)
+    kernels = {n: v / max(c, 1) for n, (c, v) in prof.items() if c > 0}
+    # algorithmic HBM bytes per launch of the router kernel: x once, logits once, router weights once
+    router_bytes = w.T * w.d_model * 4 + w.T * w.E * 4 + w.E * w.d_model * 4
+    gbs = router_bytes / (kernels["router_scores"] * 1e-3) / 1e9
+    return {"workload": w.name, "ms_per_step": ms, "mtokens_per_s": w.T / (ms * 1e-3) / 1e6,
+            "kernel_ms": {n: round(v, 5) for n, v in kernels.items()},
+            "router_roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                                "frac": gbs / PEAK_HBM_GBS, "bytes_per_launch": router_bytes}}
 
 
 def cpu_baseline(w, mode, dev, n_sample):

@@ -80,7 +80,7 @@ static int make_dims(const rr_config *c, bool need_ffn, Dims *D) {
   if (rmax > ((int64_t)1 << 28)) return RR_ERR_UNSUPPORTED;
   D->Rmax = (int)rmax;
   D->BM = c->dtype == RR_BF16 ? 256 : 64;
-  D->max_mtiles = D->Rmax / D->BM + c->E;
+  D->max_mtiles = need_ffn ? D->Rmax / D->BM + c->E : 0;  // routing-only calls cut no GEMM row tiles
   return RR_OK;
 }
 
@@ -111,8 +111,8 @@ static size_t carve(const Dims &D, bool forward, void *ws, Work *W) {
   W->ir_blk_cnt = cv.take<int32_t>(E * D.NB);
   W->ir_cnt = cv.take<int32_t>(E);
   W->row_base = cv.take<int32_t>(E + 1);
-  W->tile_expert = cv.take<int32_t>(D.max_mtiles);
-  W->tile_row0 = cv.take<int32_t>(D.max_mtiles);
+  W->tile_expert = cv.take<int32_t>(D.max_mtiles + 1);
+  W->tile_row0 = cv.take<int32_t>(D.max_mtiles + 1);
   W->n_tiles = cv.take<int32_t>(1);
   if (forward) {
     size_t K1 = D.k + 1, es = D.dtype == RR_BF16 ? 2 : 4;

@@ -59,8 +59,18 @@ __global__ __launch_bounds__(kTokBlock) void topk_rank_kernel(const float *__res
   const int t0 = b * kTokBlock;
   const int ntok = min(kTokBlock, A.T - t0);
   const int E = A.E;
-  const float *src = logits + (size_t)t0 * E;
-  for (int idx = tid; idx < ntok * E; idx += kTokBlock) {
+  const float *src = logits + (size_t)t0 * E;  // 16-byte aligned: t0 is a multiple of 128
+  const int nvec = (ntok * E) >> 2;
+  for (int v = tid; v < nvec; v += kTokBlock) {
+    const float4 q = reinterpret_cast<const float4 *>(src)[v];
+    const float qq[4] = {q.x, q.y, q.z, q.w};
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      int idx = 4 * v + u, row = idx / E, e = idx - row * E;
+      tile[row * TS + e] = qq[u];
+    }
+  }
+  for (int idx = 4 * nvec + tid; idx < ntok * E; idx += kTokBlock) {
     int row = idx / E, e = idx - row * E;
     tile[row * TS + e] = src[idx];
   }
@@ -325,30 +335,38 @@ __global__ __launch_bounds__(kTokBlock) void ir_count_kernel(DispatchArgs A, con
 }
 
 // Dispatched-row layout: expert e owns rows [row_base[e], row_base[e+1]): its occupied capacity
-// slots first, then its Intra-GPU rows.  Also cuts every expert's rows into tiles of BM rows.
+// slots first, then its Intra-GPU rows.  Also cuts every expert's rows into tiles of BM rows
+// (skipped when max_mtiles == 0: routing-only calls have no grouped GEMM).
 __global__ __launch_bounds__(64) void row_plan_kernel(DispatchArgs A, const int32_t *__restrict__ fill_total,
                                                       const int32_t *__restrict__ ir_cnt,
                                                       int32_t *__restrict__ ir_offset, int32_t *__restrict__ row_base,
                                                       int32_t *__restrict__ tile_expert,
                                                       int32_t *__restrict__ tile_row0, int32_t *__restrict__ n_tiles) {
-  if (threadIdx.x != 0) return;
-  int off = 0, base = 0, nt = 0;
-  for (int e = 0; e < A.E; ++e) {
-    int nir = A.ir ? ir_cnt[e] : 0;
-    ir_offset[e] = off;
-    row_base[e] = base;
-    int rows = fill_total[e] + nir;
-    for (int m0 = 0; m0 < rows && nt < A.max_mtiles; m0 += A.BM) {
-      tile_expert[nt] = e;
-      tile_row0[nt] = m0;
-      ++nt;
-    }
-    off += nir;
-    base += rows;
+  const int e = threadIdx.x;  // one lane per expert, E <= 64 = one wave
+  const bool on = e < A.E;
+  const int nir = (on && A.ir) ? ir_cnt[e] : 0;
+  const int rows = on ? fill_total[e] + nir : 0;
+  const int tiles = A.max_mtiles > 0 ? (rows + A.BM - 1) / A.BM : 0;
+  int s_ir = nir, s_rows = rows, s_tiles = tiles;  // inclusive scans over experts
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    int a = __shfl_up(s_ir, off), b = __shfl_up(s_rows, off), c = __shfl_up(s_tiles, off);
+    if (e >= off) { s_ir += a; s_rows += b; s_tiles += c; }
   }
-  ir_offset[A.E] = off;
-  row_base[A.E] = base;
-  *n_tiles = nt;
+  if (on) {
+    ir_offset[e] = s_ir - nir;
+    row_base[e] = s_rows - rows;
+    int t = s_tiles - tiles;
+    for (int m0 = 0; m0 < rows && tiles > 0 && t < A.max_mtiles; m0 += A.BM, ++t) {
+      tile_expert[t] = e;
+      tile_row0[t] = m0;
+    }
+  }
+  if (e == A.E - 1) {
+    ir_offset[A.E] = s_ir;
+    row_base[A.E] = s_rows;
+    *n_tiles = min(s_tiles, A.max_mtiles);
+  }
 }
 
 // Per token: Intra-GPU list position (Sec. 4.1) and the Eq. 2 / Eq. 3 weights.

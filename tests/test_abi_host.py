@@ -1,0 +1,140 @@
+"""CPU-only checks of the C ABI: the library loads, exports every function the header declares, and
+its host-side argument validation returns the documented codes before anything touches a GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2402_12399_amd as rr
+from oracle import rectify_router as orc
+from paper_2402_12399_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+RR_OK, INVALID, UNSUPPORTED, WORKSPACE = 0, -1, -2, -3
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(rr.library_path()):
+        from paper_2402_12399_amd import build
+        build.build(verbose=False)
+    return rr.load_library()
+
+
+def test_every_declared_function_is_exported(lib):
+    header = open(os.path.join(ROOT, "include", "rr.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(rr_[a-z_]+)\s*\(", header))
+    assert {"rr_capacity", "rr_workspace_bytes", "rr_router_scores", "rr_rectified_dispatch", "rr_moe_forward",
+            "rr_profile_enable", "rr_profile_read", "rr_strerror"} <= declared
+    for name in declared:
+        assert hasattr(lib, name), f"{name} declared in rr.h but not exported by librr.so"
+
+
+def test_struct_layout_matches_header():
+    # rr_config: six int32, float, two int32, uint32; rr_tables: ten pointers
+    assert C.sizeof(binding._Config) == 40
+    assert C.sizeof(binding._Tables) == 10 * C.sizeof(C.c_void_p)
+
+
+def test_capacity_matches_oracle_definition():
+    rng = np.random.default_rng(0)
+    for _ in range(2000):
+        T, E = int(rng.integers(1, 1 << 20)), int(rng.integers(1, 65))
+        cf = float(np.float32(rng.choice([0.25, 0.5, 0.75, 1.0, 1.1, 1.25, 1.5, 2.0, 2.5, 3.0, 0.001, 7.3])))
+        assert rr.rr_capacity(T, E, cf) == orc.capacity(T, E, cf), (T, E, cf)
+    assert rr.rr_capacity(0, 8, 1.0) == -1 and rr.rr_capacity(8, 0, 1.0) == -1
+    assert rr.rr_capacity(8, 8, 0.0) == -1 and rr.rr_capacity(8, 8, float("nan")) == -1
+
+
+def test_strerror(lib):
+    assert rr.rr_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -99):
+        assert rr.rr_strerror(code)
+
+
+def _cfg(**kw):
+    base = dict(T=1024, d_model=64, d_ff=128, E=8, k=2, G=2, capacity_factor=1.0, dtype=rr.RR_BF16,
+                act=rr.RR_ACT_SWIGLU, flags=rr.RR_INTRA_GPU | rr.RR_FILL_IN)
+    base.update(kw)
+    return rr.RRConfig(**base)
+
+
+def _ws_status(lib, cfg):
+    n = C.c_size_t(0)
+    cc = cfg.c()
+    return lib.rr_workspace_bytes(C.byref(cc), C.byref(n)), n.value
+
+
+@pytest.mark.parametrize("kw,want", [
+    (dict(), RR_OK),
+    (dict(E=6, G=4), INVALID),             # E % G
+    (dict(T=1001), INVALID),               # T % G
+    (dict(k=9, E=8), INVALID),             # k > E
+    (dict(k=2, E=2, G=1), INVALID),        # Fill-in needs a (k+1)-th expert
+    (dict(k=2, E=2, G=1, flags=rr.RR_INTRA_GPU), RR_OK),
+    (dict(T=0), INVALID), (dict(G=0), INVALID), (dict(capacity_factor=0.0), INVALID),
+    (dict(flags=64), INVALID),
+    (dict(E=128, G=2), UNSUPPORTED), (dict(k=5, E=8), UNSUPPORTED), (dict(dtype=7), UNSUPPORTED),
+    (dict(d_model=60), UNSUPPORTED), (dict(d_ff=100), UNSUPPORTED), (dict(act=5), UNSUPPORTED),
+    (dict(T=1 << 25, G=2), UNSUPPORTED),
+])
+def test_config_validation(lib, kw, want):
+    assert _ws_status(lib, _cfg(**kw))[0] == want
+
+
+def test_workspace_size_properties(lib):
+    rc, small = _ws_status(lib, _cfg(d_ff=0))
+    rc2, full = _ws_status(lib, _cfg())
+    assert rc == rc2 == RR_OK and small % 256 == 0 and full % 256 == 0 and full > small > 0
+    assert _ws_status(lib, _cfg(T=2048))[1] > full
+    cc = _cfg().c()
+    assert lib.rr_workspace_bytes(C.byref(cc), None) == INVALID
+    assert lib.rr_workspace_bytes(None, C.byref(C.c_size_t(0))) == INVALID
+
+
+def test_entry_points_reject_bad_arguments_on_the_host(lib):
+    """Nothing here reaches a kernel launch: every call fails validation first."""
+    cfg = _cfg()
+    cc = cfg.c()
+    fake = C.c_void_p(0x1000)  # never dereferenced: validation fails before any launch
+    tables = binding._Tables(*([0x1000] * 10))
+    # NULL data pointers
+    assert lib.rr_router_scores(C.byref(cc), None, fake, None, fake, None, None, None) == INVALID
+    assert lib.rr_router_scores(C.byref(cc), fake, fake, None, None, None, None, None) == INVALID
+    assert lib.rr_rectified_dispatch(C.byref(cc), None, C.byref(tables), fake, 1 << 30, None) == INVALID
+    holes = binding._Tables(*([0x1000] * 9 + [0]))
+    assert lib.rr_rectified_dispatch(C.byref(cc), fake, C.byref(holes), fake, 1 << 30, None) == INVALID
+    # workspace: missing, misaligned, too small
+    assert lib.rr_rectified_dispatch(C.byref(cc), fake, C.byref(tables), None, 1 << 30, None) == WORKSPACE
+    assert lib.rr_rectified_dispatch(C.byref(cc), fake, C.byref(tables), C.c_void_p(0x1010), 1 << 30, None) == WORKSPACE
+    assert lib.rr_rectified_dispatch(C.byref(cc), fake, C.byref(tables), fake, 256, None) == WORKSPACE
+    # forward: missing up-projection for SwiGLU, missing output, invalid config
+    assert lib.rr_moe_forward(C.byref(cc), fake, fake, None, fake, None, fake, fake, None, None, fake, 1 << 40, None) == INVALID
+    assert lib.rr_moe_forward(C.byref(cc), fake, fake, None, fake, fake, fake, None, None, None, fake, 1 << 40, None) == INVALID
+    assert lib.rr_moe_forward(C.byref(cc), fake, fake, None, fake, fake, fake, fake, None, None, fake, 256, None) == WORKSPACE
+    bad = _cfg(E=6, G=4).c()
+    assert lib.rr_moe_forward(C.byref(bad), fake, fake, None, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == INVALID
+    nofnn = _cfg(d_ff=0).c()
+    assert lib.rr_moe_forward(C.byref(nofnn), fake, fake, None, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == INVALID
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(binding, "_LIB", None)
+    monkeypatch.setattr(binding, "_HERE", "/nonexistent")
+    with pytest.raises(rr.RRError):
+        rr.rr_capacity(8, 8, 1.0)
+
+
+def test_product_path_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2402_12399_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"^\s*(from|import)\s+oracle\b", text, flags=re.M), f"{f} imports the oracle"
+                assert "oracle/" not in text and "rectify_router" not in text, f"{f} refers to the oracle's files"
+    oracle_src = open(os.path.join(ROOT, "oracle", "rectify_router.py")).read()
+    assert "paper_2402_12399_amd" not in oracle_src
