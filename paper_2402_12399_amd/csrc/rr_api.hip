@@ -111,9 +111,8 @@ static size_t carve(const Dims &D, bool forward, void *ws, Work *W) {
   W->ir_blk_cnt = cv.take<int32_t>(E * D.NB);
   W->ir_cnt = cv.take<int32_t>(E);
   W->row_base = cv.take<int32_t>(E + 1);
-  W->tile_expert = cv.take<int32_t>(D.max_mtiles + 1);
-  W->tile_row0 = cv.take<int32_t>(D.max_mtiles + 1);
-  W->n_tiles = cv.take<int32_t>(1);
+  W->tiles = cv.take<TileInfo>(D.max_mtiles + 1);
+  W->tile_ctl = cv.take<int32_t>(4);
   if (forward) {
     size_t K1 = D.k + 1, es = D.dtype == RR_BF16 ? 2 : 4;
     W->logits = cv.take<float>(T * E);
@@ -214,8 +213,8 @@ int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, c
   float *lg = logits ? logits : W.logits;
   hipError_t e = launch_router(D, x, w_router, bias, lg, nullptr, nullptr, s);
   if (e == hipSuccess) e = launch_dispatch(D, lg, tb, W, s);
-  if (e == hipSuccess) e = launch_gather(D, x, tb, W, s);
-  if (e == hipSuccess) e = launch_ffn(D, w1, w3, w2, W, s);
+  if (e == hipSuccess && !ffn_fuses_gather(D)) e = launch_gather(D, x, tb, W, s);
+  if (e == hipSuccess) e = launch_ffn(D, x, tb, w1, w3, w2, W, s);
   if (e == hipSuccess) e = launch_combine(D, tb, W, out, s);
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
 }

@@ -340,14 +340,14 @@ __global__ __launch_bounds__(kTokBlock) void ir_count_kernel(DispatchArgs A, con
 __global__ __launch_bounds__(64) void row_plan_kernel(DispatchArgs A, const int32_t *__restrict__ fill_total,
                                                       const int32_t *__restrict__ ir_cnt,
                                                       int32_t *__restrict__ ir_offset, int32_t *__restrict__ row_base,
-                                                      int32_t *__restrict__ tile_expert,
-                                                      int32_t *__restrict__ tile_row0, int32_t *__restrict__ n_tiles) {
+                                                      TileInfo *__restrict__ tiles, int32_t *__restrict__ tile_ctl) {
   const int e = threadIdx.x;  // one lane per expert, E <= 64 = one wave
   const bool on = e < A.E;
   const int nir = (on && A.ir) ? ir_cnt[e] : 0;
-  const int rows = on ? fill_total[e] + nir : 0;
-  const int tiles = A.max_mtiles > 0 ? (rows + A.BM - 1) / A.BM : 0;
-  int s_ir = nir, s_rows = rows, s_tiles = tiles;  // inclusive scans over experts
+  const int fill = on ? fill_total[e] : 0;
+  const int rows = fill + nir;
+  const int ntile = A.max_mtiles > 0 ? (rows + A.BM - 1) / A.BM : 0;
+  int s_ir = nir, s_rows = rows, s_tiles = ntile;  // inclusive scans over experts
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     int a = __shfl_up(s_ir, off), b = __shfl_up(s_rows, off), c = __shfl_up(s_tiles, off);
@@ -356,16 +356,14 @@ __global__ __launch_bounds__(64) void row_plan_kernel(DispatchArgs A, const int3
   if (on) {
     ir_offset[e] = s_ir - nir;
     row_base[e] = s_rows - rows;
-    int t = s_tiles - tiles;
-    for (int m0 = 0; m0 < rows && tiles > 0 && t < A.max_mtiles; m0 += A.BM, ++t) {
-      tile_expert[t] = e;
-      tile_row0[t] = m0;
-    }
+    int t = s_tiles - ntile;
+    for (int m0 = 0; m0 < rows && ntile > 0 && t < A.max_mtiles; m0 += A.BM, ++t)
+      tiles[t] = TileInfo{e, m0, s_rows - rows, rows, fill, s_ir - nir, 0, 0};
   }
   if (e == A.E - 1) {
     ir_offset[A.E] = s_ir;
     row_base[A.E] = s_rows;
-    *n_tiles = min(s_tiles, A.max_mtiles);
+    tile_ctl[0] = min(s_tiles, A.max_mtiles);
   }
 }
 
@@ -470,8 +468,7 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     prof_end(K_IR_SCAN, s);
   }
   prof_begin(K_ROW_PLAN, s);
-  row_plan_kernel<<<1, 64, 0, s>>>(A, tb.fill_total, W.ir_cnt, tb.ir_offset, W.row_base, W.tile_expert, W.tile_row0,
-                                   W.n_tiles);
+  row_plan_kernel<<<1, 64, 0, s>>>(A, tb.fill_total, W.ir_cnt, tb.ir_offset, W.row_base, W.tiles, W.tile_ctl);
   prof_end(K_ROW_PLAN, s);
   prof_begin(K_IR_WEIGHTS, s);
   ir_weights_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.key, W.ir_score, W.ir_cand, W.ir_blk_cnt, tb.ir_offset,

@@ -31,6 +31,13 @@ struct Dims {
   int BM;          // row-tile height of the grouped GEMM for this dtype
 };
 
+// One row tile of the grouped GEMM: rows [row0, row0 + BM) of expert `expert`, whose dispatched rows
+// start at `rbase` and number `rows` (`fill` occupied capacity slots, then the Intra-GPU rows, whose
+// tokens start at ir_token[ir_offset]).
+struct __attribute__((aligned(32))) TileInfo {
+  int32_t expert, row0, rbase, rows, fill, ir_offset, pad0, pad1;
+};
+
 // Device pointers carved out of the caller's workspace.
 struct Work {
   // routing
@@ -47,9 +54,8 @@ struct Work {
   int32_t *ir_blk_cnt;   // [E, NB]   Intra-GPU tokens per (expert, token block); scanned in place
   int32_t *ir_cnt;       // [E]
   int32_t *row_base;     // [E+1]     first dispatched row of each expert (slot rows, then IR rows)
-  int32_t *tile_expert;  // [max_mtiles] row tiles of the grouped GEMM
-  int32_t *tile_row0;    // [max_mtiles] first row of the tile, relative to row_base[expert]
-  int32_t *n_tiles;      // [1]
+  TileInfo *tiles;       // [max_mtiles] row tiles of the grouped GEMM
+  int32_t *tile_ctl;     // [4] [0] = number of row tiles
   // forward only
   float   *logits;       // [T,E] when the caller passes none
   rr_tables tables;      // storage when the caller passes none
@@ -88,7 +94,9 @@ hipError_t launch_router(const Dims &D, const void *x, const float *w_router, co
                          float *logits, float *probs, int32_t *rank_expert, hipStream_t s);
 hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, hipStream_t s);
 hipError_t launch_gather(const Dims &D, const void *x, const rr_tables &tb, const Work &W, hipStream_t s);
-hipError_t launch_ffn(const Dims &D, const void *w1, const void *w3, const void *w2, const Work &W, hipStream_t s);
+bool ffn_fuses_gather(const Dims &D);  // the up projection reads x through the dispatch tables: no gather pass
+hipError_t launch_ffn(const Dims &D, const void *x, const rr_tables &tb, const void *w1, const void *w3,
+                      const void *w2, const Work &W, hipStream_t s);
 hipError_t launch_combine(const Dims &D, const rr_tables &tb, const Work &W, void *out, hipStream_t s);
 
 }  // namespace rr
