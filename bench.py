@@ -160,7 +160,7 @@ def main():
 
 def routing_stress(rr, wl, torch, steps, warmup):
     """Routing-only workload (1M fp32 tokens, 64 experts in 8 groups, top-2, capacity factor 0.75):
-    rr_router_scores + rr_rectified_dispatch, the memory-bound part of the path."""
+    rr_moe_forward with d_ff = 0, i.e. router scores through combine weights, the memory-bound part of the path."""
     w = wl.C4
     cfg = rr.RRConfig(w.T, w.d_model, 0, w.E, w.k, w.G, w.capacity_factor, rr.RR_F32, rr.RR_ACT_SWIGLU,
                       rr.RR_INTRA_GPU | rr.RR_FILL_IN)
@@ -169,9 +169,8 @@ def routing_stress(rr, wl, torch, steps, warmup):
     tables = rr.alloc_tables(cfg)
     ws = rr.alloc_workspace(cfg)
 
-    def step():
-        rr.rr_router_scores(cfg, dev["x"], dev["w_router"], dev["bias"], logits)
-        rr.rr_rectified_dispatch(cfg, logits, tables, ws)
+    def step():  # d_ff = 0: router (with fused ranking) + routing tables, no expert FFN
+        rr.rr_moe_forward(cfg, dev["x"], dev["w_router"], dev["bias"], None, None, None, None, tables, logits, ws)
 
     for _ in range(warmup):
         step()

@@ -120,6 +120,8 @@ int rr_rectified_dispatch(const rr_config *cfg, const float *logits, const rr_ta
  *       carried by the transformer block's residual connection, Sec. 3)
  *   tables: NULL, or tables to fill as rr_rectified_dispatch does
  *   logits: NULL, or [T,E] fp32 out
+ * With cfg->d_ff == 0 the call stops after the tables (routing only: router and ranking fused, the
+ * logits are not read back): tables and logits are then required, w1, w3, w2 and out are ignored.
  */
 int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, const float *bias,
                    const void *w1, const void *w3, const void *w2, void *out,

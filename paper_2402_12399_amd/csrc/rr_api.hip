@@ -177,7 +177,8 @@ int rr_router_scores(const rr_config *cfg, const void *x, const float *w_router,
   int rc = make_dims(cfg, false, &D);
   if (rc != RR_OK) return rc;
   if (!x || !w_router || !logits) return RR_ERR_INVALID_ARG;
-  hipError_t e = launch_router(D, x, w_router, bias, logits, probs, rank_expert, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_router(D, x, w_router, bias, logits, probs, rank_expert, nullptr, nullptr,
+                               static_cast<hipStream_t>(stream));
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
 }
 
@@ -191,28 +192,36 @@ int rr_rectified_dispatch(const rr_config *cfg, const float *logits, const rr_ta
   memset(&W, 0, sizeof(W));
   rc = check_ws(D, false, workspace, workspace_bytes, &W);
   if (rc != RR_OK) return rc;
-  hipError_t e = launch_dispatch(D, logits, *out, W, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_dispatch(D, logits, *out, W, false, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
 }
 
 int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, const float *bias, const void *w1,
                    const void *w3, const void *w2, void *out, const rr_tables *tables, float *logits,
                    void *workspace, size_t workspace_bytes, void *stream) {
+  if (!cfg) return RR_ERR_INVALID_ARG;
+  const bool routing_only = cfg->d_ff == 0;  // router + tables, no expert FFN
   Dims D;
-  int rc = make_dims(cfg, true, &D);
+  int rc = make_dims(cfg, !routing_only, &D);
   if (rc != RR_OK) return rc;
-  if (!x || !w_router || !w1 || !w2 || !out) return RR_ERR_INVALID_ARG;
-  if (cfg->act == RR_ACT_SWIGLU && !w3) return RR_ERR_INVALID_ARG;
+  if (!x || !w_router) return RR_ERR_INVALID_ARG;
+  if (routing_only) {
+    if (!tables || !logits) return RR_ERR_INVALID_ARG;
+  } else {
+    if (!w1 || !w2 || !out) return RR_ERR_INVALID_ARG;
+    if (cfg->act == RR_ACT_SWIGLU && !w3) return RR_ERR_INVALID_ARG;
+  }
   if (tables && !tables_complete(tables)) return RR_ERR_INVALID_ARG;
   Work W;
   memset(&W, 0, sizeof(W));
-  rc = check_ws(D, true, workspace, workspace_bytes, &W);
+  rc = check_ws(D, !routing_only, workspace, workspace_bytes, &W);
   if (rc != RR_OK) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const rr_tables &tb = tables ? *tables : W.tables;
   float *lg = logits ? logits : W.logits;
-  hipError_t e = launch_router(D, x, w_router, bias, lg, nullptr, nullptr, s);
-  if (e == hipSuccess) e = launch_dispatch(D, lg, tb, W, s);
+  hipError_t e = launch_router(D, x, w_router, bias, lg, nullptr, nullptr, &tb, &W, s);
+  if (e == hipSuccess) e = launch_dispatch(D, lg, tb, W, router_ranks(D), s);
+  if (routing_only) return e == hipSuccess ? RR_OK : RR_ERR_HIP;
   if (e == hipSuccess && !ffn_fuses_gather(D)) e = launch_gather(D, x, tb, W, s);
   if (e == hipSuccess) e = launch_ffn(D, x, tb, w1, w3, w2, W, s);
   if (e == hipSuccess) e = launch_combine(D, tb, W, out, s);

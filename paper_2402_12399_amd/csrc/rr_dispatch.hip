@@ -439,12 +439,15 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
 
 }  // namespace
 
-hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, hipStream_t s) {
+hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, bool ranked,
+                           hipStream_t s) {
   DispatchArgs A{D.T, D.E, D.k, D.C, D.NR, D.NCAT, D.NB, D.Eg, D.Tg, D.ir, D.fr, D.arrival, D.BM, D.max_mtiles};
-  prof_begin(K_TOPK, s);
-  topk_rank_kernel<<<D.NB, kTokBlock, 0, s>>>(logits, A, tb.rank_expert, tb.slot, W.key, W.ir_score, W.ir_cand,
-                                              W.blk_cnt);
-  prof_end(K_TOPK, s);
+  if (!ranked) {  // otherwise the router's epilogue has already written what topk_rank writes
+    prof_begin(K_TOPK, s);
+    topk_rank_kernel<<<D.NB, kTokBlock, 0, s>>>(logits, A, tb.rank_expert, tb.slot, W.key, W.ir_score, W.ir_cand,
+                                                W.blk_cnt);
+    prof_end(K_TOPK, s);
+  }
   prof_begin(K_SCAN_CAND, s);
   scan_blocks_kernel<<<D.NCAT, 256, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NB);
   prof_end(K_SCAN_CAND, s);

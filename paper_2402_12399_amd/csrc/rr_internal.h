@@ -90,9 +90,14 @@ __host__ __device__ inline float key_score(u32 key) {
 }
 
 // Stage launchers (each returns a hipError_t from the launches it made).
+// With tb and W the router may also do the per-token ranking that the routing tables start from
+// (router_ranks(D) says whether it does); launch_dispatch is then told to skip that step.
+bool router_ranks(const Dims &D);
 hipError_t launch_router(const Dims &D, const void *x, const float *w_router, const float *bias,
-                         float *logits, float *probs, int32_t *rank_expert, hipStream_t s);
-hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, hipStream_t s);
+                         float *logits, float *probs, int32_t *rank_expert, const rr_tables *tb, const Work *W,
+                         hipStream_t s);
+hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, bool ranked,
+                           hipStream_t s);
 hipError_t launch_gather(const Dims &D, const void *x, const rr_tables &tb, const Work &W, hipStream_t s);
 bool ffn_fuses_gather(const Dims &D);  // the up projection reads x through the dispatch tables: no gather pass
 hipError_t launch_ffn(const Dims &D, const void *x, const rr_tables &tb, const void *w1, const void *w3,

@@ -212,6 +212,243 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
   }
 }
 
+// ------------------------------------------------------------------ large batches
+// Streaming variant: a workgroup of 4 waves owns 256 tokens, each wave 64 of them over the whole K
+// (no K split, no reduction).  The router weights go through LDS: every 64-wide K chunk of w is
+// split into its three bf16 parts ONCE per workgroup (not once per wave) and stored as MFMA
+// operand rows (128-byte rows, chunk c of row r at position c ^ ((r >> 1) & 7), as in the grouped
+// GEMM); x still streams global -> registers, one K chunk (64 bytes per lane) ahead.  One barrier
+// per chunk.
+// With a RankOut the epilogue also does the per-token work that the routing tables start from
+// (ranking, score keys, best expert of the token's own group, candidate counts per 128-token
+// block), so the logits are not read back from HBM.
+struct RankOut {
+  int32_t *rank_expert, *slot;  // [T,k+1]
+  u32 *key;                     // [T,NR]
+  float *ir_score;              // [T]
+  int32_t *ir_cand;             // [T]
+  int32_t *blk_cnt;             // [NCAT, NB]
+  int k, NR, fr, Eg, Tg, NCAT, NB;
+};
+
+constexpr int RS_TM = 2;                     // 32-token fragments per wave
+constexpr int RS_TB = RT_NW * RS_TM * 32;    // 256 tokens per workgroup
+static_assert(RS_TB == 2 * kTokBlock, "a workgroup covers exactly two 128-token blocks of the routing kernels");
+
+template <bool BF16, int NJ, bool FUSE>
+__global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *__restrict__ xv,
+                                                                   const float *__restrict__ wr,
+                                                                   const float *__restrict__ bias,
+                                                                   float *__restrict__ logits, float *__restrict__ probs,
+                                                                   int32_t *__restrict__ rank_expert, int T, int d, int E,
+                                                                   int k, RankOut R) {
+  constexpr int TM = RS_TM;
+  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int KC = BF16 ? 64 : 32;          // K chunk: a lane covers KC/2 elements = 64 bytes of its row
+  constexpr int XQ = KC * ES / 32;            // uint4 loads per lane per fragment per chunk (= 4)
+  constexpr int ROWS = NJ * 32;               // expert rows staged
+  constexpr int ROWB = KC * 2;                // bytes of a staged bf16 row
+  constexpr int NCH = ROWB / 16;              // 16-byte chunks per row: 8 (swizzle (r>>1)&7) or 4 ((r>>2)&3)
+  constexpr int PART = ROWS * ROWB;           // bytes of one bf16 part of a chunk
+  constexpr int STAGE = 3 * PART;
+  constexpr int WLD = ROWS * (KC / 4) / RT_THREADS;  // float4 loads of w per thread per chunk
+  constexpr int TSTR = ROWS + 1;              // row stride of the per-wave [32 tokens][experts] epilogue tile
+  constexpr int TILE_BYTES = RT_NW * 32 * TSTR * 4;  // the epilogue tiles reuse the weight stages
+  __shared__ __attribute__((aligned(16))) char lds[2 * STAGE > TILE_BYTES ? 2 * STAGE : TILE_BYTES];
+  __shared__ int cnt[2][kMaxRounds * kMaxE];
+  __shared__ float row_max[RT_NW][32], row_inv[RT_NW][32];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int fr = lane & 31, fh = lane >> 5;
+  auto swz = [](int r) { return NCH == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); };
+  const int fsw = swz(fr);
+  const int t0 = blockIdx.x * RS_TB, tw0 = t0 + w * TM * 32;
+  const int nchunk = (d + KC - 1) / KC;
+
+  const char *xrow[TM];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+    xrow[i] = static_cast<const char *>(xv) + (size_t)min(tw0 + i * 32 + fr, T - 1) * d * ES;
+
+  // ---- w staging: thread owns float4 (4 consecutive k) number tid + 256 q of the [ROWS][KC] chunk
+  float4 wreg[WLD];
+  auto load_w = [&](int kc) {
+#pragma unroll
+    for (int q = 0; q < WLD; ++q) {
+      const int idx = tid + q * RT_THREADS, e = idx / (KC / 4), kk = kc + (idx % (KC / 4)) * 4;
+      wreg[q] = (e < E && kk < d) ? *reinterpret_cast<const float4 *>(wr + (size_t)e * d + kk) : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+  };
+  auto store_w = [&](int stage) {
+    char *st = lds + stage * STAGE;
+#pragma unroll
+    for (int q = 0; q < WLD; ++q) {
+      const int idx = tid + q * RT_THREADS, e = idx / (KC / 4), f4 = idx % (KC / 4);
+      u32 h0, l0, m0, h1, l1, m1;
+      split_pair(wreg[q].x, wreg[q].y, h0, l0, m0);
+      split_pair(wreg[q].z, wreg[q].w, h1, l1, m1);
+      // 8 bytes (4 bf16) at k offset f4*4: 16-byte chunk f4/2, half f4%2
+      const int off = e * ROWB + (((f4 >> 1) ^ swz(e)) << 4) + (f4 & 1) * 8;
+      *reinterpret_cast<uint2 *>(st + off) = make_uint2(h0, h1);
+      *reinterpret_cast<uint2 *>(st + PART + off) = make_uint2(l0, l1);
+      *reinterpret_cast<uint2 *>(st + 2 * PART + off) = make_uint2(m0, m1);
+    }
+  };
+
+  uint4 xr[TM][XQ], xn[TM][XQ];
+  auto load_x = [&](int kc, uint4 (&dst)[TM][XQ]) {
+    const int k0 = kc + fh * (KC / 2);  // this lane's half of the chunk
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int q = 0; q < XQ; ++q) {
+        const int kq = k0 + q * (16 / ES);
+        dst[i][q] = kq < d ? *reinterpret_cast<const uint4 *>(xrow[i] + (size_t)kq * ES) : make_uint4(0, 0, 0, 0);
+      }
+  };
+
+  f32x16 acc[TM][NJ];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < NJ; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+  load_w(0);
+  load_x(0, xr);
+  store_w(0);
+  for (int c = 0; c < nchunk; ++c) {
+    __syncthreads();  // stage c & 1 is complete; the other stage is no longer read
+    const bool more = c + 1 < nchunk;
+    if (more) { load_w((c + 1) * KC); load_x((c + 1) * KC, xn); }
+    const char *st = lds + (c & 1) * STAGE;
+    // lane (row fr, half fh) holds elements [fh*KC/2 + 8 m, +8) of the chunk at k-step m: 16-byte chunk (KC/16) fh + m
+#pragma unroll
+    for (int m = 0; m < KC / 16; ++m) {
+      const int pos = (((KC / 16) * fh + m) ^ fsw) << 4;
+      Frag wh[NJ], wl[NJ], wl2[NJ];
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        const char *rowp = st + (j * 32 + fr) * ROWB + pos;
+        wh[j].v = *reinterpret_cast<const bf16x8 *>(rowp);
+        wl[j].v = *reinterpret_cast<const bf16x8 *>(rowp + PART);
+        wl2[j].v = *reinterpret_cast<const bf16x8 *>(rowp + 2 * PART);
+      }
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+        if (BF16) {
+          Frag xf;
+          xf.w[0] = xr[i][m].x; xf.w[1] = xr[i][m].y; xf.w[2] = xr[i][m].z; xf.w[3] = xr[i][m].w;
+#pragma unroll
+          for (int j = 0; j < NJ; ++j) {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wl2[j].v, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wl[j].v, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wh[j].v, acc[i][j], 0, 0, 0);
+          }
+        } else {
+          Frag xh, xl, xl2;
+          split8(xr[i][2 * m], xr[i][2 * m + 1], xh, xl, xl2);
+#pragma unroll
+          for (int j = 0; j < NJ; ++j) {  // smallest products first
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl2.v, wh[j].v, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wl2[j].v, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, wl[j].v, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, wh[j].v, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wl[j].v, acc[i][j], 0, 0, 0);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wh[j].v, acc[i][j], 0, 0, 0);
+          }
+        }
+      }
+    }
+    if (more) {
+      store_w((c + 1) & 1);
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int q = 0; q < XQ; ++q) xr[i][q] = xn[i][q];
+    }
+  }
+  __syncthreads();  // the weight stages become the epilogue tiles
+
+  // ---- epilogue, one 32-token fragment at a time through this wave's LDS tile
+  float *tile = reinterpret_cast<float *>(lds) + w * 32 * TSTR;
+  if (FUSE) {
+    for (int c = tid; c < 2 * kMaxRounds * kMaxE; c += RT_THREADS) (&cnt[0][0])[c] = 0;
+    __syncthreads();
+  }
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+    const int tf0 = tw0 + i * 32;            // first token of the fragment
+    const int ntok = min(32, T - tf0);       // may be <= 0 for the last workgroup
+    // accumulator element v is token 8*(v/4) + 4*(lane/32) + v%4, expert lane%32
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const int e = j * 32 + fr;
+      const float b = (bias && e < E) ? bias[e] : 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) tile[(8 * (v >> 2) + 4 * fh + (v & 3)) * TSTR + e] = acc[i][j][v] + b;
+    }
+    __builtin_amdgcn_wave_barrier();
+    // logits rows of the fragment are contiguous in memory
+    for (int idx = lane; idx < ntok * E; idx += kWave) {
+      const int row = idx / E, e = idx - row * E;
+      logits[(size_t)tf0 * E + idx] = tile[row * TSTR + e];
+    }
+    if (lane < ntok) {
+      const float *row = tile + lane * TSTR;
+      const int tok = tf0 + lane;
+      if (probs) {
+        float mx = row[0];
+        for (int e = 1; e < E; ++e) mx = fmaxf(mx, row[e]);
+        float sum = 0.0f;
+        for (int e = 0; e < E; ++e) sum += expf(row[e] - mx);
+        row_max[w][lane] = mx;
+        row_inv[w][lane] = 1.0f / sum;
+      }
+      if (rank_expert || FUSE) {
+        float bs[kMaxRank];
+        int be[kMaxRank];
+        const int n = min(k + 1, E);
+        top_n_of_row(row, E, n, bs, be);
+        int32_t *ranks = FUSE ? R.rank_expert : rank_expert;
+#pragma unroll
+        for (int q = 0; q < kMaxRank; ++q) {
+          if (q <= k) ranks[(size_t)tok * (k + 1) + q] = (q < n) ? be[q] : -1;
+          if (FUSE && q < R.NR) {
+            R.key[(size_t)tok * R.NR + q] = score_key(bs[q]);
+            atomicAdd(&cnt[w >> 1][q * E + be[q]], 1);
+          }
+        }
+        if (FUSE) {
+          if (!R.fr) R.slot[(size_t)tok * (k + 1) + k] = -1;
+          const int g = tok / R.Tg;
+          float best;
+          int arg;
+          best_in_group(row, g * R.Eg, (g + 1) * R.Eg, best, arg);
+          R.ir_score[tok] = best;
+          R.ir_cand[tok] = arg;
+        }
+      }
+    }
+    if (probs) {
+      __builtin_amdgcn_wave_barrier();
+      for (int idx = lane; idx < ntok * E; idx += kWave) {
+        const int row = idx / E, e = idx - row * E;
+        probs[(size_t)tf0 * E + idx] = expf(tile[row * TSTR + e] - row_max[w][row]) * row_inv[w][row];
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+  if (FUSE) {
+    __syncthreads();
+    // waves 0,1 cover token block 2*blockIdx.x, waves 2,3 the next one
+    for (int c = tid; c < 2 * R.NCAT; c += RT_THREADS) {
+      const int half = c / R.NCAT, cat = c - half * R.NCAT, b = 2 * blockIdx.x + half;
+      if (b < R.NB) R.blk_cnt[(size_t)cat * R.NB + b] = cnt[half][cat];
+    }
+  }
+}
+
 template <bool BF16, int TM>
 void launch_one(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits, float *probs,
                 int32_t *rank_expert, hipStream_t s) {
@@ -222,19 +459,43 @@ void launch_one(const Dims &D, const void *x, const float *w_router, const float
     router_kernel<BF16, TM, 2><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k);
 }
 
+template <bool BF16>
+void launch_stream(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits, float *probs,
+                   int32_t *rank_expert, const RankOut *R, hipStream_t s) {
+  dim3 grid((D.T + RS_TB - 1) / RS_TB), block(RT_THREADS);
+  RankOut none{};
+#define RR_LAUNCH_STREAM(NJ)                                                                                        \
+  do {                                                                                                              \
+    if (R) router_stream_kernel<BF16, NJ, true><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, \
+                                                                        D.T, D.d, D.E, D.k, *R);                     \
+    else router_stream_kernel<BF16, NJ, false><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert,  \
+                                                                       D.T, D.d, D.E, D.k, none);                    \
+  } while (0)
+  if (D.E <= 32) RR_LAUNCH_STREAM(1);
+  else RR_LAUNCH_STREAM(2);
+#undef RR_LAUNCH_STREAM
+}
+
 }  // namespace
 
+bool router_ranks(const Dims &D) { return D.T > 64 * 1024; }
+
 hipError_t launch_router(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits,
-                         float *probs, int32_t *rank_expert, hipStream_t s) {
-  // 32-token tiles while the batch is small enough that larger ones would leave CUs idle
-  const bool small = D.T <= 64 * 1024;
+                         float *probs, int32_t *rank_expert, const rr_tables *tb, const Work *W, hipStream_t s) {
+  // small batches: 32-token tiles with K split across the waves, so that the launch still fills the
+  // chip; large ones: the streaming kernel
+  const bool small = !router_ranks(D);
   prof_begin(K_ROUTER, s);
-  if (D.dtype == RR_BF16) {
-    if (small) launch_one<true, 1>(D, x, w_router, bias, logits, probs, rank_expert, s);
-    else launch_one<true, 2>(D, x, w_router, bias, logits, probs, rank_expert, s);
+  if (small) {
+    if (D.dtype == RR_BF16) launch_one<true, 1>(D, x, w_router, bias, logits, probs, rank_expert, s);
+    else launch_one<false, 1>(D, x, w_router, bias, logits, probs, rank_expert, s);
   } else {
-    if (small) launch_one<false, 1>(D, x, w_router, bias, logits, probs, rank_expert, s);
-    else launch_one<false, 2>(D, x, w_router, bias, logits, probs, rank_expert, s);
+    RankOut R{};
+    if (tb && W)
+      R = RankOut{tb->rank_expert, tb->slot, W->key, W->ir_score, W->ir_cand, W->blk_cnt,
+                  D.k, D.NR, D.fr, D.Eg, D.Tg, D.NCAT, D.NB};
+    if (D.dtype == RR_BF16) launch_stream<true>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
+    else launch_stream<false>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
   }
   prof_end(K_ROUTER, s);
   return hipGetLastError();

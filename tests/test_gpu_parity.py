@@ -217,3 +217,35 @@ def test_c4_routing_full_size():
     a = wl.synthetic_logits(w.T, w.E, seed=4, bias_std=0.0)
     a *= np.float32(0.64)  # std of w.x at d_model 1024 with N(0, 0.02) router weights
     gu.assert_tables_equal(gu.run_dispatch(cfg, a), orc.route(a, w.k, w.G, w.capacity_factor, True, True))
+
+
+@pytest.mark.parametrize("dtype,E,k,G", [("f32", 64, 2, 8), ("bf16", 16, 1, 4), ("f32", 24, 4, 2)])
+def test_routing_only_forward_large_batch(dtype, E, k, G):
+    """Batches above 64K tokens take the streaming router whose epilogue also ranks (d_ff = 0: routing only).
+    Inputs are small dyadic rationals, so every dot product is exact in fp32 and in bf16 parts: the logits
+    must equal the oracle's bit for bit, ties are frequent, and the tables must match exactly."""
+    T, d = 66112 + 16 * G, 72
+    rng = np.random.default_rng(E + k)
+    x = rng.integers(-3, 4, size=(T, d)).astype(np.float32) / np.float32(2.0)
+    wr = rng.integers(-4, 5, size=(E, d)).astype(np.float32) / np.float32(8.0)
+    b = rng.integers(-8, 9, size=E).astype(np.float32) / np.float32(4.0)
+    cfg = rr.RRConfig(T, d, 0, E, k, G, 0.75, rr.RR_F32 if dtype == "f32" else rr.RR_BF16, rr.RR_ACT_SWIGLU,
+                      rr.RR_INTRA_GPU | rr.RR_FILL_IN)
+    xs = wl._store(x, dtype)
+    tb, logits = rr.alloc_tables(cfg), torch.empty((T, E), dtype=torch.float32, device="cuda")
+    ws = rr.alloc_workspace(cfg)
+    rr.rr_moe_forward(cfg, gu.to_device(xs, dtype), torch.from_numpy(wr).cuda(), torch.from_numpy(b).cuda(),
+                      None, None, None, None, tb, logits, ws)
+    torch.cuda.synchronize()
+    a = orc.router_scores(wl.values_f32(xs, dtype), wr, b)
+    assert np.array_equal(logits.cpu().numpy(), a)
+    gu.assert_tables_equal(tb.to_host(), orc.route(a, k, G, 0.75, True, True))
+    # the stand-alone router entry point takes the same kernel (without the ranking epilogue)
+    probs = torch.empty_like(logits)
+    ranks = torch.empty((T, k + 1), dtype=torch.int32, device="cuda")
+    rr.rr_router_scores(cfg, gu.to_device(xs, dtype), torch.from_numpy(wr).cuda(), torch.from_numpy(b).cuda(),
+                        logits, probs, ranks)
+    torch.cuda.synchronize()
+    assert np.array_equal(logits.cpu().numpy(), a)
+    assert np.array_equal(ranks.cpu().numpy(), orc.rank_experts(a, k + 1))
+    assert np.abs(probs.cpu().numpy() - orc.softmax_probs(a)).max() <= 1e-6
