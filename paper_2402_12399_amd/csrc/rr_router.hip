@@ -235,7 +235,8 @@ constexpr int RS_TM = 2;                     // 32-token fragments per wave
 constexpr int RS_TB = RT_NW * RS_TM * 32;    // 256 tokens per workgroup
 static_assert(RS_TB == 2 * kTokBlock, "a workgroup covers exactly two 128-token blocks of the routing kernels");
 
-template <bool BF16, int NJ, bool FUSE>
+// EXACT: d is a whole number of K chunks and E fills the staged rows, so no load needs a predicate.
+template <bool BF16, int NJ, bool FUSE, bool EXACT>
 __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *__restrict__ xv,
                                                                    const float *__restrict__ wr,
                                                                    const float *__restrict__ bias,
@@ -275,7 +276,8 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
 #pragma unroll
     for (int q = 0; q < WLD; ++q) {
       const int idx = tid + q * RT_THREADS, e = idx / (KC / 4), kk = kc + (idx % (KC / 4)) * 4;
-      wreg[q] = (e < E && kk < d) ? *reinterpret_cast<const float4 *>(wr + (size_t)e * d + kk) : make_float4(0.f, 0.f, 0.f, 0.f);
+      wreg[q] = (EXACT || (e < E && kk < d)) ? *reinterpret_cast<const float4 *>(wr + (size_t)e * d + kk)
+                                             : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
   auto store_w = [&](int stage) {
@@ -294,7 +296,9 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
     }
   };
 
-  uint4 xr[TM][XQ], xn[TM][XQ];
+  // x ring: chunk c is consumed from buffer c % 4 while chunks c+1 .. c+3 are in flight (one chunk of
+  // MFMAs is shorter than an HBM round trip; three are not)
+  uint4 xb0[TM][XQ], xb1[TM][XQ], xb2[TM][XQ], xb3[TM][XQ];
   auto load_x = [&](int kc, uint4 (&dst)[TM][XQ]) {
     const int k0 = kc + fh * (KC / 2);  // this lane's half of the chunk
 #pragma unroll
@@ -302,7 +306,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
 #pragma unroll
       for (int q = 0; q < XQ; ++q) {
         const int kq = k0 + q * (16 / ES);
-        dst[i][q] = kq < d ? *reinterpret_cast<const uint4 *>(xrow[i] + (size_t)kq * ES) : make_uint4(0, 0, 0, 0);
+        dst[i][q] = (EXACT || kq < d) ? *reinterpret_cast<const uint4 *>(xrow[i] + (size_t)kq * ES) : make_uint4(0, 0, 0, 0);
       }
   };
 
@@ -314,13 +318,14 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  load_w(0);
-  load_x(0, xr);
-  store_w(0);
-  for (int c = 0; c < nchunk; ++c) {
-    __syncthreads();  // stage c & 1 is complete; the other stage is no longer read
+  // one K chunk: x of this chunk is in `xc`; x of chunk c+3 is loaded into `xo`
+  auto chunk = [&](int c, uint4 (&xc)[TM][XQ], uint4 (&xo)[TM][XQ]) {
+    // Stage c & 1 is complete (own LDS writes: lgkmcnt 0; everybody's: barrier) and the other stage
+    // is no longer read.  Not __syncthreads(): its fence would also wait for the x loads in flight.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     const bool more = c + 1 < nchunk;
-    if (more) { load_w((c + 1) * KC); load_x((c + 1) * KC, xn); }
+    if (more) load_w((c + 1) * KC);
+    if (c + 3 < nchunk) load_x((c + 3) * KC, xo);
     const char *st = lds + (c & 1) * STAGE;
     // lane (row fr, half fh) holds elements [fh*KC/2 + 8 m, +8) of the chunk at k-step m: 16-byte chunk (KC/16) fh + m
 #pragma unroll
@@ -338,7 +343,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
       for (int i = 0; i < TM; ++i) {
         if (BF16) {
           Frag xf;
-          xf.w[0] = xr[i][m].x; xf.w[1] = xr[i][m].y; xf.w[2] = xr[i][m].z; xf.w[3] = xr[i][m].w;
+          xf.w[0] = xc[i][m].x; xf.w[1] = xc[i][m].y; xf.w[2] = xc[i][m].z; xf.w[3] = xc[i][m].w;
 #pragma unroll
           for (int j = 0; j < NJ; ++j) {
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wl2[j].v, acc[i][j], 0, 0, 0);
@@ -347,7 +352,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
           }
         } else {
           Frag xh, xl, xl2;
-          split8(xr[i][2 * m], xr[i][2 * m + 1], xh, xl, xl2);
+          split8(xc[i][2 * m], xc[i][2 * m + 1], xh, xl, xl2);
 #pragma unroll
           for (int j = 0; j < NJ; ++j) {  // smallest products first
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl2.v, wh[j].v, acc[i][j], 0, 0, 0);
@@ -360,13 +365,18 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
         }
       }
     }
-    if (more) {
-      store_w((c + 1) & 1);
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int q = 0; q < XQ; ++q) xr[i][q] = xn[i][q];
-    }
+    if (more) store_w((c + 1) & 1);
+  };
+  load_w(0);
+  load_x(0, xb0);
+  if (1 < nchunk) load_x(KC, xb1);
+  if (2 < nchunk) load_x(2 * KC, xb2);
+  store_w(0);
+  for (int c = 0; c < nchunk; c += 4) {  // four chunks per trip: the ring rotates without register copies
+    chunk(c, xb0, xb3);
+    if (c + 1 < nchunk) chunk(c + 1, xb1, xb0);
+    if (c + 2 < nchunk) chunk(c + 2, xb2, xb1);
+    if (c + 3 < nchunk) chunk(c + 3, xb3, xb2);
   }
   __syncthreads();  // the weight stages become the epilogue tiles
 
@@ -464,15 +474,20 @@ void launch_stream(const Dims &D, const void *x, const float *w_router, const fl
                    int32_t *rank_expert, const RankOut *R, hipStream_t s) {
   dim3 grid((D.T + RS_TB - 1) / RS_TB), block(RT_THREADS);
   RankOut none{};
-#define RR_LAUNCH_STREAM(NJ)                                                                                        \
+  const int KC = BF16 ? 64 : 32;
+#define RR_LAUNCH_STREAM(NJ, EXACT)                                                                                 \
   do {                                                                                                              \
-    if (R) router_stream_kernel<BF16, NJ, true><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, \
-                                                                        D.T, D.d, D.E, D.k, *R);                     \
-    else router_stream_kernel<BF16, NJ, false><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert,  \
-                                                                       D.T, D.d, D.E, D.k, none);                    \
+    if (R) router_stream_kernel<BF16, NJ, true, EXACT><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs,      \
+                                                                               rank_expert, D.T, D.d, D.E, D.k, *R); \
+    else router_stream_kernel<BF16, NJ, false, EXACT><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs,       \
+                                                                              rank_expert, D.T, D.d, D.E, D.k, none);\
   } while (0)
-  if (D.E <= 32) RR_LAUNCH_STREAM(1);
-  else RR_LAUNCH_STREAM(2);
+  const int NJ = D.E <= 32 ? 1 : 2;
+  const bool exact = D.d % KC == 0 && D.E == NJ * 32;
+  if (NJ == 1 && exact) RR_LAUNCH_STREAM(1, true);
+  else if (NJ == 1) RR_LAUNCH_STREAM(1, false);
+  else if (exact) RR_LAUNCH_STREAM(2, true);
+  else RR_LAUNCH_STREAM(2, false);
 #undef RR_LAUNCH_STREAM
 }
 
