@@ -38,12 +38,100 @@ def parse():
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--mode", default="ir+fr", help="vanilla | ir | fr | ir+fr")
     ap.add_argument("--cpu-sample", type=int, default=2048, help="tokens the CPU oracle computes outputs for (0 = skip)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the headline workload: skip the paper-shape (c3) and routing-stress (c4) extras")
     ap.add_argument("--no-routing-stress", action="store_true",
                     help="skip the extra routing-only measurement (1M tokens, 64 experts, top-2)")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters by)")
     return ap.parse_args()
+
+
+def run_forward(rr, wl, torch, w, mode, steps, warmup):
+    """Times rr_moe_forward on one workload; returns the numbers the JSON line is built from."""
+    flags = (rr.RR_INTRA_GPU if "ir" in mode else 0) | (rr.RR_FILL_IN if "fr" in mode else 0)
+    cfg = rr.RRConfig(w.T, w.d_model, w.d_ff, w.E, w.k, w.G, w.capacity_factor,
+                      rr.RR_F32 if w.dtype == "f32" else rr.RR_BF16,
+                      rr.RR_ACT_GELU if w.act == "gelu" else rr.RR_ACT_SWIGLU, flags)
+    dev = wl.make_inputs_device(w)
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    out = torch.empty((w.T, w.d_model), dtype=tdt, device="cuda")
+    tables = rr.alloc_tables(cfg)
+    logits = torch.empty((w.T, w.E), dtype=torch.float32, device="cuda")
+    ws = rr.alloc_workspace(cfg)
+
+    def step():
+        rr.rr_moe_forward(cfg, dev["x"], dev["w_router"], dev["bias"], dev["w1"], dev["w3"], dev["w2"], out,
+                          tables, logits, ws)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / steps
+
+    # per-kernel durations: the same steps again with every launch bracketed by HIP events on the
+    # launch stream
+    rr.rr_profile_enable(True)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    prof = rr.rr_profile_read()
+    ms_per_step_profiled = (time.perf_counter() - t0) * 1e3 / steps
+    rr.rr_profile_enable(False)
+    kernels = {n: ms / max(c, 1) for n, (c, ms) in prof.items() if c > 0}
+
+    th = tables.to_host()
+    C = tables.capacity
+    slot_rows = int(th["fill_total"].sum())
+    ir_rows = int(th["ir_offset"][-1])
+    R = slot_rows + ir_rows
+    es = 4 if w.dtype == "f32" else 2
+    gated = w.act == "swiglu"
+    d, F, T, E, k = w.d_model, w.d_ff, w.T, w.E, w.k
+    flops = {"ffn_gate_up": (4 if gated else 2) * d * F * R, "ffn_down": 2 * d * F * R}
+    # algorithmic HBM bytes per launch of the memory-bound kernels (each operand once)
+    n_src = int((th["slot"] >= 0).sum()) + ir_rows          # rows of y that combine reads
+    hbm = {"router_scores": T * d * es + T * E * 4 + E * d * 4,
+           "dispatch_gather": 2 * R * d * es + 4 * R,
+           "combine": (n_src + T) * d * es + T * (k + 2) * 4}
+    peak_tf = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
+    per_kernel = {}
+    for n, ms in kernels.items():
+        if n in flops:
+            tf = flops[n] / (ms * 1e-3) / 1e12
+            per_kernel[n] = {"bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": tf, "unit": "TFLOP/s",
+                             "frac": tf / peak_tf}
+        elif n in hbm:
+            gbs = hbm[n] / (ms * 1e-3) / 1e9
+            per_kernel[n] = {"bound": "hbm", "achieved": gbs, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS}
+    dom = max(kernels, key=kernels.get)
+    roofline = dict(kernel=dom, **per_kernel.get(dom, {"bound": "hbm", "achieved": None, "unit": "GB/s", "frac": None}))
+    roofline["peak"] = peak_tf if dom in flops else PEAK_HBM_GBS
+    roofline["traffic"] = MEASURED_TRAFFIC_BYTES.get((w.name, dom))
+    roofline["avg_ms"] = kernels[dom]
+    if dom in flops:
+        roofline["flops_per_launch"] = flops[dom]
+    ffn_ms = kernels.get("ffn_gate_up", 0) + kernels.get("ffn_down", 0)
+    routing_names = ("router_scores", "topk_rank", "scan_candidates", "plan_rounds", "scatter_candidates",
+                     "select_slot", "ir_count", "ir_scan", "row_plan", "ir_weights")
+    routing_ms = sum(kernels.get(n, 0.0) for n in routing_names)
+    return {
+        "dev": dev, "capacity": C, "ms_per_step": ms_per_step, "tokens_per_s": T / (ms_per_step * 1e-3),
+        "roofline": roofline, "ms_per_step_with_events": ms_per_step_profiled,
+        "kernel_ms": {n: round(v, 5) for n, v in kernels.items()},
+        "kernel_roofline": {n: {kk: (round(vv, 4) if isinstance(vv, float) else vv) for kk, vv in v.items()}
+                            for n, v in per_kernel.items()},
+        "ffn_tflops": (flops["ffn_gate_up"] + flops["ffn_down"]) / (ffn_ms * 1e-3) / 1e12 if ffn_ms else None,
+        "routing_rectify_mtokens_per_s": T / (routing_ms * 1e-3) / 1e6 if routing_ms else None,
+        "rows": {"slot_rows": slot_rows, "ir_rows": ir_rows, "capacity_slots": E * C,
+                 "dropped_assignments": int((th["slot"][:, :k] < 0).sum()),
+                 "fill_in_placed": int((th["slot"][:, k] >= 0).sum()), "padding_slots": E * C - slot_rows},
+    }
 
 
 def main():
@@ -61,68 +149,27 @@ def main():
         print("bench.py: workload has no expert FFN; use a forward workload", file=sys.stderr)
         return 2
     mode = () if args.mode == "vanilla" else tuple(args.mode.split("+"))
-    flags = (rr.RR_INTRA_GPU if "ir" in mode else 0) | (rr.RR_FILL_IN if "fr" in mode else 0)
-    cfg = rr.RRConfig(w.T, w.d_model, w.d_ff, w.E, w.k, w.G, w.capacity_factor,
-                      rr.RR_F32 if w.dtype == "f32" else rr.RR_BF16,
-                      rr.RR_ACT_GELU if w.act == "gelu" else rr.RR_ACT_SWIGLU, flags)
     torch.cuda.set_device(0)
-    dev = wl.make_inputs_device(w)
-    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
-    out = torch.empty((w.T, w.d_model), dtype=tdt, device="cuda")
-    tables = rr.alloc_tables(cfg)
-    logits = torch.empty((w.T, w.E), dtype=torch.float32, device="cuda")
-    ws = rr.alloc_workspace(cfg)
+    res = run_forward(rr, wl, torch, w, mode, args.steps, args.warmup)
+    dev = res.pop("dev")
 
-    def step():
-        rr.rr_moe_forward(cfg, dev["x"], dev["w_router"], dev["bias"], dev["w1"], dev["w3"], dev["w2"], out,
-                          tables, logits, ws)
+    cpu = None
+    if args.cpu_sample > 0:
+        cpu = cpu_baseline(w, mode, dev, min(args.cpu_sample, w.T))
+    del dev
+    torch.cuda.empty_cache()
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-
-    # per-kernel durations: the same K steps again with every launch bracketed by HIP events on
-    # the launch stream
-    rr.rr_profile_enable(True)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    prof = rr.rr_profile_read()
-    ms_per_step_profiled = (time.perf_counter() - t0) * 1e3 / args.steps
-    rr.rr_profile_enable(False)
-    kernels = {n: ms / max(c, 1) for n, (c, ms) in prof.items() if c > 0}
-
-    th = tables.to_host()
-    C = tables.capacity
-    slot_rows = int(th["fill_total"].sum())
-    ir_rows = int(th["ir_offset"][-1])
-    R = slot_rows + ir_rows
-    es = 4 if w.dtype == "f32" else 2
-    gated = w.act == "swiglu"
-    flops = {"ffn_gate_up": (4 if gated else 2) * w.d_model * w.d_ff * R, "ffn_down": 2 * w.d_model * w.d_ff * R}
-    dom = max(kernels, key=kernels.get)
-    peak_tf = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
-    if dom in flops:
-        achieved = flops[dom] / (kernels[dom] * 1e-3) / 1e12
-        roofline = {"kernel": dom, "bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": achieved,
-                    "peak": peak_tf, "unit": "TFLOP/s", "frac": achieved / peak_tf,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get((w.name, dom)),
-                    "flops_per_launch": flops[dom], "avg_ms": kernels[dom]}
-    else:
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": None, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": None, "traffic": None, "avg_ms": kernels[dom]}
-    ffn_ms = kernels.get("ffn_gate_up", 0) + kernels.get("ffn_down", 0)
-    ffn_tf = (flops["ffn_gate_up"] + flops["ffn_down"]) / (ffn_ms * 1e-3) / 1e12 if ffn_ms else None
-    routing_names = ("router_scores", "topk_rank", "scan_candidates", "plan_rounds", "scatter_candidates",
-                     "select_slot", "ir_count", "ir_scan", "row_plan", "ir_weights")
-    routing_ms = sum(kernels.get(n, 0.0) for n in routing_names)
-
-    stress = None if args.no_routing_stress else routing_stress(rr, wl, torch, args.steps, args.warmup)
+    # extras: the paper's own layer shape (LLaMA2-7B FFN, 8 experts, 16384 tokens per GPU, top-2) and
+    # the routing-only stress workload
+    paper_shape = None
+    if not args.no_extras and args.workload != "c3":
+        r3 = run_forward(rr, wl, torch, wl.C3, ("ir", "fr"), max(5, args.steps // 5), max(2, args.warmup // 5))
+        r3.pop("dev")
+        torch.cuda.empty_cache()
+        paper_shape = {"workload": wl.C3.name, "mode": "top2+ir+fr", "ms_per_step": r3["ms_per_step"],
+                       "tokens_per_s": r3["tokens_per_s"], "ffn_tflops": r3["ffn_tflops"],
+                       "kernel_ms": r3["kernel_ms"], "kernel_roofline": r3["kernel_roofline"], "rows": r3["rows"]}
+    stress = None if (args.no_routing_stress or args.no_extras) else routing_stress(rr, wl, torch, args.steps, args.warmup)
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -130,29 +177,25 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    cpu = None
-    if args.cpu_sample > 0:
-        cpu = cpu_baseline(w, mode, dev, min(args.cpu_sample, w.T))
-
     line = {
-        "metric": "rectified_moe_layer_tokens_per_s", "value": w.T / (ms_per_step * 1e-3), "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "metric": "rectified_moe_layer_tokens_per_s", "value": res["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "mode": "top%d" % w.k + "".join("+" + m for m in mode), "T": w.T,
                    "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k, "G": w.G,
-                   "capacity_factor": w.capacity_factor, "capacity": C, "act": w.act, "router": "fp32",
+                   "capacity_factor": w.capacity_factor, "capacity": res["capacity"], "act": w.act, "router": "fp32",
                    "parallelism": "1 GPU, %d simulated expert-parallel groups" % w.G},
-        "roofline": roofline,
+        "roofline": res["roofline"],
         "cpu_baseline": cpu,
-        "ms_per_step_with_events": ms_per_step_profiled,
-        "kernel_ms": {n: round(v, 5) for n, v in kernels.items()},
-        "ffn_tflops": ffn_tf,
-        "routing_rectify_mtokens_per_s": w.T / (routing_ms * 1e-3) / 1e6 if routing_ms else None,
+        "ms_per_step_with_events": res["ms_per_step_with_events"],
+        "kernel_ms": res["kernel_ms"],
+        "kernel_roofline": res["kernel_roofline"],
+        "ffn_tflops": res["ffn_tflops"],
+        "routing_rectify_mtokens_per_s": res["routing_rectify_mtokens_per_s"],
+        "rows": res["rows"],
+        "paper_shape": paper_shape,
         "routing_stress": stress,
-        "rows": {"slot_rows": slot_rows, "ir_rows": ir_rows, "capacity_slots": w.E * C,
-                 "dropped_assignments": int((th["slot"][:, :w.k] < 0).sum()),
-                 "fill_in_placed": int((th["slot"][:, w.k] >= 0).sum()), "padding_slots": w.E * C - slot_rows},
     }
     print(json.dumps(line))
     return 0
