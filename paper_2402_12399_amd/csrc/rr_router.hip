@@ -1,13 +1,16 @@
 // Router scores (Eq. 1), softmax over all experts (App. A, Eq. 5) and argtopk.
 //
 // logits[T,E] = x[T,d] . w_router[E,d]^T (+ bias) with fp32 accuracy on the bf16 matrix cores:
-// every fp32 operand is split exactly into three bf16 parts (8 + 8 + 8 mantissa bits, by
-// truncation, so hi + lo + lo2 == value) and the products that matter are accumulated in fp32 by
-// v_mfma_f32_32x32x16_bf16:
-//   bf16 x : x.w_hi + x.w_lo + x.w_lo2                                        (3 MFMAs, exact operands)
-//   fp32 x : x_hi.w_hi + x_hi.w_lo + x_lo.w_hi + x_lo.w_lo + x_hi.w_lo2 + x_lo2.w_hi   (6 MFMAs; the
-//            dropped products are below 2^-24 of the leading one)
-// This keeps the kernel bound by the one pass over x in HBM instead of by fp32 FMA throughput.
+// fp32 operands are split into bf16 parts, each the nearest bf16 (v_cvt_pk_bf16_f32) of what the
+// previous parts left over, so k parts carry 9k mantissa bits; the products that matter are
+// accumulated in fp32 by v_mfma_f32_32x32x16_bf16:
+//   w      : three parts (27 bits)
+//   bf16 x : x.w_hi + x.w_lo + x.w_lo2                                          (3 MFMAs, x exact)
+//   fp32 x : two parts (18 bits: |x - x_hi - x_lo| <= 2^-18 |x|, i.e. <= 4e-6 relative per element,
+//            ~1e-6 of a logit after the random-sign sum); x_hi.(w_hi + w_lo + w_lo2) + x_lo.(w_hi + w_lo)
+//            (5 MFMAs; a third x part would double the splitting arithmetic, which is what bounds
+//            the fp32 kernel, for accuracy below the fp32 rounding of the accumulation itself)
+// This keeps the kernel near the one pass over x in HBM instead of bound by fp32 FMA throughput.
 //
 // A workgroup of 4 waves owns TM*32 tokens; the waves split K four ways and each streams its K slice
 // straight from global memory into MFMA operand registers (no LDS in the main loop, no barriers):
@@ -34,25 +37,54 @@ union Frag {
   bf16x8 v;
 };
 
-// two fp32 values -> their three bf16 parts, packed pairwise (element 0 in the low half)
-__device__ inline void split_pair(float f0, float f1, u32 &hi, u32 &lo, u32 &lo2) {
-  const u32 b0 = __builtin_bit_cast(u32, f0), b1 = __builtin_bit_cast(u32, f1);
-  const float r0 = f0 - __builtin_bit_cast(float, b0 & 0xffff0000u);
-  const float r1 = f1 - __builtin_bit_cast(float, b1 & 0xffff0000u);
-  const u32 c0 = __builtin_bit_cast(u32, r0), c1 = __builtin_bit_cast(u32, r1);
-  const float s0 = r0 - __builtin_bit_cast(float, c0 & 0xffff0000u);
-  const float s1 = r1 - __builtin_bit_cast(float, c1 & 0xffff0000u);
-  hi = __builtin_amdgcn_perm(b1, b0, 0x07060302u);
-  lo = __builtin_amdgcn_perm(c1, c0, 0x07060302u);
-  lo2 = __builtin_amdgcn_perm(__builtin_bit_cast(u32, s1), __builtin_bit_cast(u32, s0), 0x07060302u);
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+
+// two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32), element 0 in the low half
+__device__ inline u32 pack_bf16(float a, float b) {
+  const f32x2_t f = {a, b};
+  return __builtin_bit_cast(u32, __builtin_convertvector(f, bf16x2_t));
+}
+__device__ inline float lo_half(u32 p) { return __builtin_bit_cast(float, p << 16); }
+__device__ inline float hi_half(u32 p) { return __builtin_bit_cast(float, p & 0xffff0000u); }
+
+// value = hi + lo + lo2 up to 2^-27 of the value: each part is the nearest bf16 of what is left
+// (the subtractions are exact), so three parts carry 27 bits
+__device__ inline void split3_pair(float f0, float f1, u32 &hi, u32 &lo, u32 &lo2) {
+  hi = pack_bf16(f0, f1);
+  const float r0 = f0 - lo_half(hi), r1 = f1 - hi_half(hi);
+  lo = pack_bf16(r0, r1);
+  lo2 = pack_bf16(r0 - lo_half(lo), r1 - hi_half(lo));
+}
+// value = hi + lo up to 2^-18 of the value
+__device__ inline void split2_pair(float f0, float f1, u32 &hi, u32 &lo) {
+  hi = pack_bf16(f0, f1);
+  lo = pack_bf16(f0 - lo_half(hi), f1 - hi_half(hi));
 }
 
-__device__ inline void split8(const uint4 a, const uint4 b, Frag &hi, Frag &lo, Frag &lo2) {
+__device__ inline void split3x8(const uint4 a, const uint4 b, Frag &hi, Frag &lo, Frag &lo2) {
   const u32 raw[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
   for (int p = 0; p < 4; ++p)
-    split_pair(__builtin_bit_cast(float, raw[2 * p]), __builtin_bit_cast(float, raw[2 * p + 1]), hi.w[p], lo.w[p],
-               lo2.w[p]);
+    split3_pair(__builtin_bit_cast(float, raw[2 * p]), __builtin_bit_cast(float, raw[2 * p + 1]), hi.w[p], lo.w[p],
+                lo2.w[p]);
+}
+__device__ inline void split2x8(const uint4 a, const uint4 b, Frag &hi, Frag &lo) {
+  const u32 raw[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+  for (int p = 0; p < 4; ++p)
+    split2_pair(__builtin_bit_cast(float, raw[2 * p]), __builtin_bit_cast(float, raw[2 * p + 1]), hi.w[p], lo.w[p]);
+}
+
+// acc += x . w for fp32 x in two parts and w in three: the five products above 2^-27 of the leading
+// one, smallest first
+__device__ inline f32x16 mfma5(const Frag &xh, const Frag &xl, const Frag &wh, const Frag &wl, const Frag &wl2, f32x16 acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wl2.v, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, wl.v, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, wh.v, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wl.v, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wh.v, acc, 0, 0, 0);
+  return acc;
 }
 
 template <bool BF16, int TM, int NJ>
@@ -124,7 +156,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
           a = *reinterpret_cast<const uint4 *>(wrow[j] + kw);
           b = *reinterpret_cast<const uint4 *>(wrow[j] + kw + 4);
         }
-        split8(a, b, wh[j], wl[j], wl2[j]);
+        split3x8(a, b, wh[j], wl[j], wl2[j]);
       }
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
@@ -138,17 +170,10 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wh[j].v, acc[i][j], 0, 0, 0);
           }
         } else {
-          Frag xh, xl, xl2;
-          split8(xr[i][2 * m], xr[i][2 * m + 1], xh, xl, xl2);
+          Frag xh, xl;
+          split2x8(xr[i][2 * m], xr[i][2 * m + 1], xh, xl);
 #pragma unroll
-          for (int j = 0; j < NJ; ++j) {  // smallest products first
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl2.v, wh[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wl2[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, wl[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, wh[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wl[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wh[j].v, acc[i][j], 0, 0, 0);
-          }
+          for (int j = 0; j < NJ; ++j) acc[i][j] = mfma5(xh, xl, wh[j], wl[j], wl2[j], acc[i][j]);
         }
       }
     }
@@ -286,8 +311,8 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
     for (int q = 0; q < WLD; ++q) {
       const int idx = tid + q * RT_THREADS, e = idx / (KC / 4), f4 = idx % (KC / 4);
       u32 h0, l0, m0, h1, l1, m1;
-      split_pair(wreg[q].x, wreg[q].y, h0, l0, m0);
-      split_pair(wreg[q].z, wreg[q].w, h1, l1, m1);
+      split3_pair(wreg[q].x, wreg[q].y, h0, l0, m0);
+      split3_pair(wreg[q].z, wreg[q].w, h1, l1, m1);
       // 8 bytes (4 bf16) at k offset f4*4: 16-byte chunk f4/2, half f4%2
       const int off = e * ROWB + (((f4 >> 1) ^ swz(e)) << 4) + (f4 & 1) * 8;
       *reinterpret_cast<uint2 *>(st + off) = make_uint2(h0, h1);
@@ -351,17 +376,10 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wh[j].v, acc[i][j], 0, 0, 0);
           }
         } else {
-          Frag xh, xl, xl2;
-          split8(xc[i][2 * m], xc[i][2 * m + 1], xh, xl, xl2);
+          Frag xh, xl;
+          split2x8(xc[i][2 * m], xc[i][2 * m + 1], xh, xl);
 #pragma unroll
-          for (int j = 0; j < NJ; ++j) {  // smallest products first
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl2.v, wh[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wl2[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, wl[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, wh[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wl[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wh[j].v, acc[i][j], 0, 0, 0);
-          }
+          for (int j = 0; j < NJ; ++j) acc[i][j] = mfma5(xh, xl, wh[j], wl[j], wl2[j], acc[i][j]);
         }
       }
     }
