@@ -94,6 +94,14 @@ __device__ inline void store_tile(f32x16 (&acc)[WM][WN], uint16_t *Cb, int rbase
 
 __device__ inline int swz(int r) { return (r >> 1) & 7; }
 
+// Barrier that publishes LDS-DMA data: the wave's own buffer_load ... lds must have written LDS
+// (vmcnt 0) before it signals.  The compiler's barrier only orders what its memory model knows to
+// be LDS traffic (lgkmcnt), so the wait is spelled out.
+__device__ inline void dma_barrier() {
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+}
+
 // ------------------------------------------------------------------ bf16, persistent, LDS DMA
 constexpr int PK_WAVES_M = 2, PK_WAVES_N = 4, PK_WM = 4, PK_WN = 2;
 constexpr int PK_NW = PK_WAVES_M * PK_WAVES_N;
@@ -253,7 +261,7 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
       for (int j = 0; j < WN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    __syncthreads();  // chunk 0 has landed (own loads: vmcnt 0; everybody's: barrier)
+    dma_barrier();  // chunk 0 has landed (own loads: vmcnt 0; everybody's: barrier)
 #pragma unroll
     for (int i = 0; i < NIA; ++i) tok1[i] = -1;
     if (GATHER && have1) lookup_tokens(info1, tok1);
@@ -305,7 +313,7 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
       step(st0, 3, 1, 0);
       for (int kt = 1; kt < KT; ++kt) {
         // chunk kt has landed and nobody reads the other stage any more
-        __syncthreads();
+        dma_barrier();
         const char *st = smem + ((par + kt) & 1) * PK_STAGE;
         load_frags(st, 0, 0);
         __builtin_amdgcn_sched_barrier(0);

@@ -260,7 +260,10 @@ constexpr int RS_TM = 2;                     // 32-token fragments per wave
 constexpr int RS_TB = RT_NW * RS_TM * 32;    // 256 tokens per workgroup
 static_assert(RS_TB == 2 * kTokBlock, "a workgroup covers exactly two 128-token blocks of the routing kernels");
 
-// EXACT: d is a whole number of K chunks and E fills the staged rows, so no load needs a predicate.
+// EXACT: d is a whole number of four-chunk ring trips and E fills the staged rows.  No load needs a
+// predicate and none sits behind a branch (prefetches past the last chunk re-read the last chunk
+// instead), so every chunk issues the same loads and the compiler's counted waits stay exact: a
+// chunk waits for its own data only, not for the three chunks in flight behind it.
 template <bool BF16, int NJ, bool FUSE, bool EXACT>
 __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *__restrict__ xv,
                                                                    const float *__restrict__ wr,
@@ -296,8 +299,11 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
     xrow[i] = static_cast<const char *>(xv) + (size_t)min(tw0 + i * 32 + fr, T - 1) * d * ES;
 
   // ---- w staging: thread owns float4 (4 consecutive k) number tid + 256 q of the [ROWS][KC] chunk
-  float4 wreg[WLD];
-  auto load_w = [&](int kc) {
+  // Two register sets: the weights of chunk c+2 are fetched during chunk c and written to LDS at
+  // the end of chunk c+1.  Loads complete in order, so a weight load that had to be complete within
+  // its own chunk would also drain every x load issued before it and flatten the x ring.
+  float4 wbuf0[WLD], wbuf1[WLD];
+  auto load_w = [&](int kc, float4 (&wreg)[WLD]) {
 #pragma unroll
     for (int q = 0; q < WLD; ++q) {
       const int idx = tid + q * RT_THREADS, e = idx / (KC / 4), kk = kc + (idx % (KC / 4)) * 4;
@@ -305,7 +311,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
                                              : make_float4(0.f, 0.f, 0.f, 0.f);
     }
   };
-  auto store_w = [&](int stage) {
+  auto store_w = [&](int stage, const float4 (&wreg)[WLD]) {
     char *st = lds + stage * STAGE;
 #pragma unroll
     for (int q = 0; q < WLD; ++q) {
@@ -343,14 +349,24 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-  // one K chunk: x of this chunk is in `xc`; x of chunk c+3 is loaded into `xo`
-  auto chunk = [&](int c, uint4 (&xc)[TM][XQ], uint4 (&xo)[TM][XQ]) {
+  // one K chunk: x of this chunk is in `xc`; x of chunk c+3 is loaded into `xo`, the weights of
+  // chunk c+2 into `wo`; `wn` holds the weights of chunk c+1
+  auto chunk = [&](int c, uint4 (&xc)[TM][XQ], uint4 (&xo)[TM][XQ], float4 (&wn)[WLD], float4 (&wo)[WLD]) {
     // Stage c & 1 is complete (own LDS writes: lgkmcnt 0; everybody's: barrier) and the other stage
     // is no longer read.  Not __syncthreads(): its fence would also wait for the x loads in flight.
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    const bool more = c + 1 < nchunk;
-    if (more) load_w((c + 1) * KC);
-    if (c + 3 < nchunk) load_x((c + 3) * KC, xo);
+    const bool more = EXACT || c + 1 < nchunk;
+    if (EXACT) {
+      load_w(min(c + 2, nchunk - 1) * KC, wo);
+      load_x(min(c + 3, nchunk - 1) * KC, xo);
+    } else {
+      if (c + 2 < nchunk) load_w((c + 2) * KC, wo);
+      if (c + 3 < nchunk) load_x((c + 3) * KC, xo);
+    }
+    // the loads are issued here, ahead of this chunk's arithmetic, and the weights of the next chunk
+    // are touched after it: left alone, the scheduler sinks the former and hoists the latter until
+    // the two meet and nothing is in flight for long
+    __builtin_amdgcn_sched_barrier(0);
     const char *st = lds + (c & 1) * STAGE;
     // lane (row fr, half fh) holds elements [fh*KC/2 + 8 m, +8) of the chunk at k-step m: 16-byte chunk (KC/16) fh + m
 #pragma unroll
@@ -383,18 +399,20 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
         }
       }
     }
-    if (more) store_w((c + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);
+    if (more) store_w((c + 1) & 1, wn);
   };
-  load_w(0);
+  load_w(0, wbuf0);
+  if (EXACT || 1 < nchunk) load_w(KC, wbuf1);
   load_x(0, xb0);
-  if (1 < nchunk) load_x(KC, xb1);
-  if (2 < nchunk) load_x(2 * KC, xb2);
-  store_w(0);
-  for (int c = 0; c < nchunk; c += 4) {  // four chunks per trip: the ring rotates without register copies
-    chunk(c, xb0, xb3);
-    if (c + 1 < nchunk) chunk(c + 1, xb1, xb0);
-    if (c + 2 < nchunk) chunk(c + 2, xb2, xb1);
-    if (c + 3 < nchunk) chunk(c + 3, xb3, xb2);
+  if (EXACT || 1 < nchunk) load_x(KC, xb1);
+  if (EXACT || 2 < nchunk) load_x(2 * KC, xb2);
+  store_w(0, wbuf0);
+  for (int c = 0; c < nchunk; c += 4) {  // four chunks per trip: the rings rotate without register copies
+    chunk(c, xb0, xb3, wbuf1, wbuf0);
+    if (EXACT || c + 1 < nchunk) chunk(c + 1, xb1, xb0, wbuf0, wbuf1);
+    if (EXACT || c + 2 < nchunk) chunk(c + 2, xb2, xb1, wbuf1, wbuf0);
+    if (EXACT || c + 3 < nchunk) chunk(c + 3, xb3, xb2, wbuf0, wbuf1);
   }
   __syncthreads();  // the weight stages become the epilogue tiles
 
@@ -501,7 +519,7 @@ void launch_stream(const Dims &D, const void *x, const float *w_router, const fl
                                                                               rank_expert, D.T, D.d, D.E, D.k, none);\
   } while (0)
   const int NJ = D.E <= 32 ? 1 : 2;
-  const bool exact = D.d % KC == 0 && D.E == NJ * 32;
+  const bool exact = D.d % (4 * KC) == 0 && D.E == NJ * 32;
   if (NJ == 1 && exact) RR_LAUNCH_STREAM(1, true);
   else if (NJ == 1) RR_LAUNCH_STREAM(1, false);
   else if (exact) RR_LAUNCH_STREAM(2, true);
