@@ -41,6 +41,15 @@ __device__ inline unsigned long long same_expert_mask(bool valid, int e) {
   return mask;
 }
 
+// Workgroup -> token block for kernels whose neighbouring token blocks write neighbouring words of
+// the same per-expert arrays.  Workgroups are dealt to the 8 XCDs round-robin and each XCD has its
+// own L2: with block = workgroup, one cache line would be completed piecewise from 8 L2s.  Here XCD
+// x walks its own contiguous eighth of the blocks, so the pieces of a line meet in one L2.
+__device__ inline int xcd_block(int g, int NB) {
+  const int per = NB >> 3, main = per << 3;
+  return g < main ? (g & 7) * per + (g >> 3) : g;
+}
+
 __device__ inline int lanes_below(unsigned long long mask) {
   int lane = lane_id();
   return __popcll(mask & ((1ull << lane) - 1ull));
@@ -104,16 +113,34 @@ __global__ __launch_bounds__(kTokBlock) void topk_rank_kernel(const float *__res
 }
 
 // ------------------------------------------------------------------ scan over token blocks
-// One workgroup per list: exclusive scan of a[list][0..NB) in place, total to tot[list].
-__global__ __launch_bounds__(256) void scan_blocks_kernel(int32_t *__restrict__ a, int32_t *__restrict__ tot, int NB) {
-  __shared__ int wsum[4];
+// One workgroup per list: exclusive scan of a[list][0..NB) in place, total to tot[list].  A thread
+// scans SC_PER consecutive entries in registers, so 8192 entries are one trip with two barriers.
+constexpr int SC_THREADS = 1024, SC_PER = 8, SC_WAVES = SC_THREADS / kWave;
+__global__ __launch_bounds__(SC_THREADS) void scan_blocks_kernel(int32_t *__restrict__ a, int32_t *__restrict__ tot,
+                                                                 int NB) {
+  __shared__ int wsum[SC_WAVES];
   int32_t *p = a + (size_t)blockIdx.x * NB;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const bool vec = (NB & 3) == 0;  // then every list starts 16-byte aligned
   int running = 0;
-  for (int base = 0; base < NB; base += 256) {
-    int idx = base + tid;
-    int v = idx < NB ? p[idx] : 0;
-    int incl = v;
+  for (int base = 0; base < NB; base += SC_THREADS * SC_PER) {
+    const int idx = base + tid * SC_PER;
+    int v[SC_PER];
+    if (vec && idx + SC_PER <= NB) {
+      const int4 q0 = *reinterpret_cast<const int4 *>(p + idx), q1 = *reinterpret_cast<const int4 *>(p + idx + 4);
+      v[0] = q0.x; v[1] = q0.y; v[2] = q0.z; v[3] = q0.w; v[4] = q1.x; v[5] = q1.y; v[6] = q1.z; v[7] = q1.w;
+    } else {
+#pragma unroll
+      for (int u = 0; u < SC_PER; ++u) v[u] = idx + u < NB ? p[idx + u] : 0;
+    }
+    int sum = 0;
+#pragma unroll
+    for (int u = 0; u < SC_PER; ++u) {  // v[u] becomes the exclusive prefix inside the thread
+      const int t = v[u];
+      v[u] = sum;
+      sum += t;
+    }
+    int incl = sum;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
       int t = __shfl_up(incl, off);
@@ -123,12 +150,20 @@ __global__ __launch_bounds__(256) void scan_blocks_kernel(int32_t *__restrict__ 
     __syncthreads();
     int before = 0, total = 0;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
+    for (int q = 0; q < SC_WAVES; ++q) {
       int s = wsum[q];
       if (q < w) before += s;
       total += s;
     }
-    if (idx < NB) p[idx] = running + before + incl - v;
+    const int off0 = running + before + incl - sum;
+    if (vec && idx + SC_PER <= NB) {
+      *reinterpret_cast<int4 *>(p + idx) = make_int4(off0 + v[0], off0 + v[1], off0 + v[2], off0 + v[3]);
+      *reinterpret_cast<int4 *>(p + idx + 4) = make_int4(off0 + v[4], off0 + v[5], off0 + v[6], off0 + v[7]);
+    } else {
+#pragma unroll
+      for (int u = 0; u < SC_PER; ++u)
+        if (idx + u < NB) p[idx + u] = off0 + v[u];
+    }
     running += total;
     __syncthreads();
   }
@@ -173,7 +208,7 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
                                                                        int32_t *__restrict__ cand_tok) {
   constexpr int NW = kTokBlock / kWave;
   __shared__ int wcnt[kMaxRounds][NW][kMaxE];
-  const int tid = threadIdx.x, b = blockIdx.x, w = tid >> 6;
+  const int tid = threadIdx.x, b = xcd_block(blockIdx.x, A.NB), w = tid >> 6;
   const int i = b * kTokBlock + tid;
   const bool valid = i < A.T;
   for (int c = tid; c < kMaxRounds * NW * kMaxE; c += kTokBlock) (&wcnt[0][0][0])[c] = 0;
@@ -380,7 +415,7 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
                                                                float *__restrict__ combine_w) {
   constexpr int NW = kTokBlock / kWave;
   __shared__ int wcnt[NW][kMaxE];
-  const int tid = threadIdx.x, b = blockIdx.x, w = tid >> 6;
+  const int tid = threadIdx.x, b = xcd_block(blockIdx.x, A.NB), w = tid >> 6;
   const int i = b * kTokBlock + tid;
   const bool valid = i < A.T;
   for (int c = tid; c < NW * kMaxE; c += kTokBlock) (&wcnt[0][0])[c] = 0;
@@ -449,7 +484,7 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     prof_end(K_TOPK, s);
   }
   prof_begin(K_SCAN_CAND, s);
-  scan_blocks_kernel<<<D.NCAT, 256, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NB);
+  scan_blocks_kernel<<<D.NCAT, SC_THREADS, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NB);
   prof_end(K_SCAN_CAND, s);
   prof_begin(K_PLAN, s);
   plan_rounds_kernel<<<1, 64, 0, s>>>(A, W.cat_cnt, W.cat_m, W.cat_fill0, W.cat_base, tb.fill_topk, tb.fill_total);
@@ -467,7 +502,7 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     ir_count_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.ir_cand, W.ir_blk_cnt);
     prof_end(K_IR_COUNT, s);
     prof_begin(K_IR_SCAN, s);
-    scan_blocks_kernel<<<D.E, 256, 0, s>>>(W.ir_blk_cnt, W.ir_cnt, D.NB);
+    scan_blocks_kernel<<<D.E, SC_THREADS, 0, s>>>(W.ir_blk_cnt, W.ir_cnt, D.NB);
     prof_end(K_IR_SCAN, s);
   }
   prof_begin(K_ROW_PLAN, s);
