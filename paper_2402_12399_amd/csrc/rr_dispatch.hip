@@ -244,6 +244,52 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
 // ------------------------------------------------------------------ select_slot
 constexpr int SS_THREADS = 1024;
 constexpr int SS_WAVES = SS_THREADS / kWave;
+constexpr int SS_PER = 24;  // keys a thread keeps in registers: lists up to 24576 candidates take the register path
+
+// m-th largest key among those that `each` enumerates, by 8-bit digits from the top (Sec. 3: the
+// lowest scores are dropped).  Returns the threshold key; need_eq = how many of the keys equal to it
+// are kept (the first ones in token order).  `each(f)` calls f(key) for every key of the calling
+// thread; all threads of the workgroup call this together.
+template <class Each>
+__device__ inline u32 radix_select(int m, Each each, u32 *hist, u32 *s_pick, u32 &need_eq) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  u32 prefix = 0, remaining = (u32)m;
+  for (int pass = 3; pass >= 0; --pass) {
+    const int shift = pass * 8;
+    if (tid < 256) hist[tid] = 0;
+    __syncthreads();
+    each([&](u32 kx) {
+      const bool match = pass == 3 || ((kx ^ prefix) >> (shift + 8)) == 0;
+      if (match) atomicAdd(&hist[(kx >> shift) & 255u], 1u);
+    });
+    __syncthreads();
+    if (w == 0) {
+      // lane l owns bins 255-4l .. 252-4l, i.e. bins in descending order across lanes
+      u32 c0 = hist[255 - 4 * lane], c1 = hist[254 - 4 * lane], c2 = hist[253 - 4 * lane], c3 = hist[252 - 4 * lane];
+      u32 sum = c0 + c1 + c2 + c3, incl = sum;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        u32 t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+      }
+      u32 excl = incl - sum;
+      if (excl < remaining && remaining <= incl) {
+        u32 rem = remaining - excl;
+        int bkt = 255 - 4 * lane;
+        if (rem > c0) { rem -= c0; --bkt;
+          if (rem > c1) { rem -= c1; --bkt;
+            if (rem > c2) { rem -= c2; --bkt; } } }
+        s_pick[0] = (u32)bkt;
+        s_pick[1] = rem;
+      }
+    }
+    __syncthreads();  // the picks are next written two barriers from here: no barrier needed after reading them
+    prefix |= s_pick[0] << shift;
+    remaining = s_pick[1];
+  }
+  need_eq = remaining;
+  return prefix;
+}
 
 __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A, const int32_t *__restrict__ cat_cnt,
                                                                  const int32_t *__restrict__ cat_m,
@@ -254,99 +300,137 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
                                                                  int32_t *__restrict__ slot,
                                                                  int32_t *__restrict__ slot_token) {
   __shared__ u32 hist[256];
-  __shared__ u32 s_bucket, s_remaining;
-  __shared__ int wtot[SS_WAVES][2];
+  __shared__ u32 s_pick[2];
+  __shared__ int2 wtot[SS_PER][SS_WAVES];  // (kept-for-sure, equal-to-threshold) counts per (trip, wave)
+  __shared__ int2 wsum[8];
   const int cat = blockIdx.x, r = cat / A.E, j = cat - r * A.E;
   const int n = cat_cnt[cat], m = cat_m[cat], fill0 = cat_fill0[cat];
   const u32 *keys = cand_key + cat_base[cat];
   const int32_t *toks = cand_tok + cat_base[cat];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const bool by_score = !A.arrival || r == A.k;  // the Fill-in round always selects by score (Sec. 4.2)
+  const unsigned long long below = (1ull << lane) - 1ull;
 
   // mode 0: nobody kept; 1: everybody kept; 2: the first m in token order; 3: by score threshold
-  int mode = m == 0 ? 0 : (m == n ? 1 : (by_score ? 3 : 2));
+  const int mode = m == 0 ? 0 : (m == n ? 1 : (by_score ? 3 : 2));
   u32 thr = 0, need_eq = 0;
-  if (mode == 3) {
-    // m-th largest key by 8-bit digits from the top; `remaining` = how many are still to be taken
-    // from the keys that match the digits fixed so far
-    u32 prefix = 0, remaining = (u32)m;
-    for (int pass = 3; pass >= 0; --pass) {
-      const int shift = pass * 8;
-      if (tid < 256) hist[tid] = 0;
-      __syncthreads();
-      for (int idx = tid; idx < n; idx += SS_THREADS) {
-        u32 kx = keys[idx];
-        bool match = pass == 3 || ((kx ^ prefix) >> (shift + 8)) == 0;
-        if (match) atomicAdd(&hist[(kx >> shift) & 255u], 1u);
-      }
-      __syncthreads();
-      if (w == 0) {
-        // lane l owns bins 255-4l .. 252-4l, i.e. bins in descending order across lanes
-        u32 c0 = hist[255 - 4 * lane], c1 = hist[254 - 4 * lane], c2 = hist[253 - 4 * lane], c3 = hist[252 - 4 * lane];
-        u32 s = c0 + c1 + c2 + c3, incl = s;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-          u32 t = __shfl_up(incl, off);
-          if (lane >= off) incl += t;
-        }
-        u32 excl = incl - s;
-        if (excl < remaining && remaining <= incl) {
-          u32 rem = remaining - excl;
-          int bkt = 255 - 4 * lane;
-          if (rem > c0) { rem -= c0; --bkt;
-            if (rem > c1) { rem -= c1; --bkt;
-              if (rem > c2) { rem -= c2; --bkt; } } }
-          s_bucket = (u32)bkt;
-          s_remaining = rem;
-        }
-      }
-      __syncthreads();
-      prefix |= s_bucket << shift;
-      remaining = s_remaining;
-      __syncthreads();
-    }
-    thr = prefix;
-    need_eq = remaining;  // of the keys equal to thr, the first need_eq in token order are kept
-  }
 
-  int run_gt = 0, run_eq = 0;
-  for (int base = 0; base < n; base += SS_THREADS) {
-    const int idx = base + tid;
-    const bool valid = idx < n;
-    u32 kx = 0;
-    int tok = 0;
-    if (valid) { kx = keys[idx]; tok = toks[idx]; }
-    bool gt, eq = false;
-    if (mode == 3) { gt = valid && kx > thr; eq = valid && kx == thr; }
-    else if (mode == 2) gt = valid && idx < m;
-    else gt = valid && mode == 1;
-    unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
-    unsigned long long below = (1ull << lane) - 1ull;
-    int gt_before = __popcll(bgt & below), eq_before = __popcll(beq & below);
-    if (lane == 0) { wtot[w][0] = __popcll(bgt); wtot[w][1] = __popcll(beq); }
-    __syncthreads();
-    int tot_gt = 0, tot_eq = 0;
+  if (n <= SS_THREADS * SS_PER) {
+    // Register path: candidate idx = u * SS_THREADS + tid is element u of thread tid.  Keys are read
+    // once; the four digit passes run on registers; the token-order prefix of the kept flags is one
+    // scan over the (trip, wave) totals instead of a barrier pair per trip.
+    const int nu = (n + SS_THREADS - 1) / SS_THREADS;
+    u32 kreg[SS_PER];
+    int treg[SS_PER];
 #pragma unroll
-    for (int q = 0; q < SS_WAVES; ++q) {
-      int a = wtot[q][0], c = wtot[q][1];
-      if (q < w) { gt_before += a; eq_before += c; }
-      tot_gt += a; tot_eq += c;
+    for (int u = 0; u < SS_PER; ++u) {
+      const int idx = u * SS_THREADS + tid;
+      kreg[u] = 0;
+      treg[u] = 0;
+      if (u < nu && idx < n) {
+        if (mode == 3) kreg[u] = keys[idx];
+        treg[u] = toks[idx];
+      }
     }
-    if (valid) {
-      int eqs = run_eq + eq_before;                       // equal keys before this one
-      bool kept = gt || (eq && (u32)eqs < need_eq);
-      int kept_before = run_gt + gt_before + min(eqs, (int)need_eq);
-      int s = fill0 + kept_before;
-      slot[(size_t)tok * (A.k + 1) + r] = kept ? s : -1;
-      if (kept) slot_token[(size_t)j * A.C + s] = tok;
+    if (mode == 3)
+      thr = radix_select(m, [&](auto f) {
+#pragma unroll
+        for (int u = 0; u < SS_PER; ++u)
+          if (u < nu && u * SS_THREADS + tid < n) f(kreg[u]);
+      }, hist, s_pick, need_eq);
+
+    int pre[SS_PER];  // lanes of this wave before this one: kept-for-sure | equal << 8
+#pragma unroll
+    for (int u = 0; u < SS_PER; ++u) {
+      pre[u] = 0;
+      if (u < nu) {
+        const int idx = u * SS_THREADS + tid;
+        const bool valid = idx < n;
+        bool gt, eq = false;
+        if (mode == 3) { gt = valid && kreg[u] > thr; eq = valid && kreg[u] == thr; }
+        else if (mode == 2) gt = valid && idx < m;
+        else gt = valid && mode == 1;
+        const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+        pre[u] = __popcll(bgt & below) | (__popcll(beq & below) << 8) | (gt ? 1 << 16 : 0) | (eq ? 1 << 17 : 0);
+        if (lane == 0) wtot[u][w] = make_int2(__popcll(bgt), __popcll(beq));
+      }
     }
-    run_gt += tot_gt;
-    run_eq += tot_eq;
     __syncthreads();
+    // exclusive scan of the nu * SS_WAVES totals in (trip, wave) order = token order
+    const int ne = nu * SS_WAVES;
+    int2 mine = make_int2(0, 0), incl = mine;
+    if (tid < ne) mine = (&wtot[0][0])[tid];
+    if (tid < 8 * kWave) {  // SS_PER * SS_WAVES = 384 entries fit 6 waves
+      incl = mine;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        const int tx = __shfl_up(incl.x, off), ty = __shfl_up(incl.y, off);
+        if (lane >= off) { incl.x += tx; incl.y += ty; }
+      }
+      if (lane == 63) wsum[w] = incl;
+    }
+    __syncthreads();
+    if (tid < ne) {
+      int2 before = make_int2(0, 0);
+      for (int q = 0; q < w; ++q) { before.x += wsum[q].x; before.y += wsum[q].y; }
+      (&wtot[0][0])[tid] = make_int2(before.x + incl.x - mine.x, before.y + incl.y - mine.y);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < SS_PER; ++u) {
+      if (u < nu && u * SS_THREADS + tid < n) {
+        const int2 base = wtot[u][w];
+        const bool gt = (pre[u] >> 16) & 1, eq = (pre[u] >> 17) & 1;
+        const int eqs = base.y + ((pre[u] >> 8) & 255);  // equal keys before this one
+        const bool kept = gt || (eq && (u32)eqs < need_eq);
+        const int sl = fill0 + base.x + (pre[u] & 255) + min(eqs, (int)need_eq);
+        slot[(size_t)treg[u] * (A.k + 1) + r] = kept ? sl : -1;
+        if (kept) slot_token[(size_t)j * A.C + sl] = treg[u];
+      }
+    }
+  } else {
+    if (mode == 3)
+      thr = radix_select(m, [&](auto f) {
+        for (int idx = tid; idx < n; idx += SS_THREADS) f(keys[idx]);
+      }, hist, s_pick, need_eq);
+    int run_gt = 0, run_eq = 0;
+    for (int base = 0; base < n; base += SS_THREADS) {
+      const int idx = base + tid;
+      const bool valid = idx < n;
+      u32 kx = 0;
+      int tok = 0;
+      if (valid) { kx = keys[idx]; tok = toks[idx]; }
+      bool gt, eq = false;
+      if (mode == 3) { gt = valid && kx > thr; eq = valid && kx == thr; }
+      else if (mode == 2) gt = valid && idx < m;
+      else gt = valid && mode == 1;
+      unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+      int gt_before = __popcll(bgt & below), eq_before = __popcll(beq & below);
+      if (lane == 0) wtot[0][w] = make_int2(__popcll(bgt), __popcll(beq));
+      __syncthreads();
+      int tot_gt = 0, tot_eq = 0;
+#pragma unroll
+      for (int q = 0; q < SS_WAVES; ++q) {
+        const int2 t = wtot[0][q];
+        if (q < w) { gt_before += t.x; eq_before += t.y; }
+        tot_gt += t.x; tot_eq += t.y;
+      }
+      if (valid) {
+        int eqs = run_eq + eq_before;                       // equal keys before this one
+        bool kept = gt || (eq && (u32)eqs < need_eq);
+        int kept_before = run_gt + gt_before + min(eqs, (int)need_eq);
+        int sl = fill0 + kept_before;
+        slot[(size_t)tok * (A.k + 1) + r] = kept ? sl : -1;
+        if (kept) slot_token[(size_t)j * A.C + sl] = tok;
+      }
+      run_gt += tot_gt;
+      run_eq += tot_eq;
+      __syncthreads();
+    }
   }
   // the last round of an expert pads the rest of its queue (Sec. 3: zero padding)
   if (r == A.NR - 1)
-    for (int s = fill0 + m + tid; s < A.C; s += SS_THREADS) slot_token[(size_t)j * A.C + s] = -1;
+    for (int sl = fill0 + m + tid; sl < A.C; sl += SS_THREADS) slot_token[(size_t)j * A.C + sl] = -1;
 }
 
 // ------------------------------------------------------------------ Intra-GPU lists
