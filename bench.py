@@ -6,6 +6,9 @@ rectification -> dispatch gather -> expert FFN grouped GEMM -> weighted combine)
 synthetic batch that is already resident in HBM.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c5|c1] [--mode ir+fr]
+    python bench.py --cf-sweep      # tokens/s against the capacity factor (the shape of Tables 3-5)
+    python bench.py --workload c4   # only the routing-only stress workload
+    python bench.py --probes        # what library kernels reach on this machine: HBM read/copy rate, dense bf16 GEMM
 """
 from __future__ import annotations
 
@@ -26,7 +29,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # profiles/bench_c2_forward_hbm_traffic.md.  Keyed by (workload, kernel); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
     ("c2_top1_bf16_zipf1.1", "ffn_gate_up"): 2432.5e6 + 114.7e6,
-    ("c2_top1_bf16_zipf1.1", "ffn_down"): 733.1e6 + 42.8e6,
+    ("c2_top1_bf16_zipf1.1", "ffn_down"): 1468.4e6 + 41.7e6,
 }
 
 
@@ -45,7 +48,39 @@ def parse():
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size kernel to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters by)")
+    ap.add_argument("--cf-sweep", action="store_true",
+                    help="instead of the benchmark line: layer tokens/s at the paper's layer shape over the capacity "
+                         "factors of Tables 3 and 4 (top-1, top-2; vanilla, Intra-GPU, Fill-in, both) and the "
+                         "experts-per-GPU settings of Table 5")
+    ap.add_argument("--probes", action="store_true",
+                    help="instead of the benchmark line: attainable rates of this box from library kernels (torch): a "
+                         "4 GiB reduction and a 1 GiB copy for HBM, dense bf16 matmuls at the expert-FFN shapes for MFMA")
     return ap.parse_args()
+
+
+def dispatch_bytes(T, E, k, NR, C, n_ir):
+    """Algorithmic HBM bytes per launch of the routing / rectification kernels: every table they read or
+    write, once, 4 bytes per entry (token blocks of 128 for the per-block candidate counts)."""
+    NB = (T + 127) // 128
+    NCAT = NR * E
+    return {
+        "topk_rank": 4 * (T * E + T * (k + 1) + T * NR + 2 * T + NCAT * NB),
+        "scan_candidates": 4 * 2 * NCAT * NB,
+        "scatter_candidates": 4 * (2 * T * NR + NCAT * NB + 2 * T * NR),
+        "select_slot": 4 * (2 * T * NR + T * NR + E * C),
+        "ir_count": 4 * (T * (k + 1) + T + E * NB),
+        "ir_scan": 4 * 2 * E * NB,
+        "ir_weights": 4 * (T * (k + 1) + T * NR + 2 * T + E * NB + 2 * T + n_ir + T * (k + 2)),
+    }
+
+
+def hbm_rooflines(kernels, hbm):
+    out = {}
+    for n, ms in kernels.items():
+        if n in hbm:
+            gbs = hbm[n] / (ms * 1e-3) / 1e9
+            out[n] = {"bound": "hbm", "achieved": round(gbs, 1), "unit": "GB/s", "frac": round(gbs / PEAK_HBM_GBS, 4)}
+    return out
 
 
 def run_forward(rr, wl, torch, w, mode, steps, warmup):
@@ -99,6 +134,7 @@ def run_forward(rr, wl, torch, w, mode, steps, warmup):
     hbm = {"router_scores": T * d * es + T * E * 4 + E * d * 4,
            "dispatch_gather": 2 * R * d * es + 4 * R,
            "combine": (n_src + T) * d * es + T * (k + 2) * 4}
+    hbm.update(dispatch_bytes(T, E, k, k + (1 if "fr" in mode else 0), C, ir_rows))
     peak_tf = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
     per_kernel = {}
     for n, ms in kernels.items():
@@ -134,6 +170,84 @@ def run_forward(rr, wl, torch, w, mode, steps, warmup):
     }
 
 
+def probes(torch):
+    """Rates that library kernels reach on this machine, as context for the roofline fractions (the peaks the
+    fractions are quoted against are the published ones)."""
+    def timed(fn, n=10):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    out = {"metric": "library_kernel_rates", "n_gpus": 1, "data": "synthetic"}
+    big = torch.ones(1 << 30, dtype=torch.float32, device="cuda")  # 4 GiB
+    out["hbm_read_GBs_torch_sum_4GiB"] = round(big.numel() * 4 / timed(lambda: big.sum()) / 1e9, 1)
+    src = big[: 1 << 28]
+    dst = torch.empty_like(src)
+    out["hbm_copy_GBs_1GiB_read_plus_write"] = round(2 * src.numel() * 4 / timed(lambda: dst.copy_(src)) / 1e9, 1)
+    del big, src, dst
+    mm = {}
+    for (M, N, K) in ((8192, 8192, 8192), (32768, 22016, 4096), (32768, 4096, 11008), (10240, 11264, 2048),
+                      (10240, 2048, 5632)):
+        a = torch.randn((M, K), device="cuda", dtype=torch.bfloat16)
+        b = torch.randn((N, K), device="cuda", dtype=torch.bfloat16)
+        mm["M%d_N%d_K%d" % (M, N, K)] = round(2 * M * N * K / timed(lambda: a @ b.t()) / 1e12, 1)
+        del a, b
+    out["dense_bf16_matmul_TFLOPs"] = mm
+    return out
+
+
+def cf_sweep(rr, wl, torch, steps, warmup):
+    """Layer throughput against the capacity factor at the paper's layer shape (Sec. 5.1: LLaMA2-7B FFN,
+    8 experts, 16384 tokens): the speed columns of Tables 3 and 4 (capacity factors 0.5-1.5 for top-1,
+    1.0-3.0 for top-2 x vanilla / Intra-GPU / Fill-in / both) and the experts-per-GPU rows of Table 5
+    (Intra-GPU at 1, 2, 4 experts per GPU).  Same synthetic tensors for every point."""
+    import dataclasses
+    base = wl.C3
+    dev = wl.make_inputs_device(base)
+    out = torch.empty((base.T, base.d_model), dtype=torch.bfloat16, device="cuda")
+    logits = torch.empty((base.T, base.E), dtype=torch.float32, device="cuda")
+    modes = {"vanilla": 0, "ir": rr.RR_INTRA_GPU, "fr": rr.RR_FILL_IN, "ir+fr": rr.RR_INTRA_GPU | rr.RR_FILL_IN}
+    points = [(1, cf, 2, m) for cf in (0.5, 0.75, 1.0, 1.25, 1.5) for m in modes]
+    points += [(2, cf, 2, m) for cf in (1.0, 1.5, 2.0, 2.5, 3.0) for m in modes]
+    points += [(k, cf, G, "ir") for (k, cf) in ((1, 1.0), (2, 2.0)) for G in (8, 4)]  # 1 and 2 experts per GPU
+    rows = []
+    for k, cf, G, m in points:
+        w = dataclasses.replace(base, k=k, capacity_factor=cf, G=G)
+        cfg = rr.RRConfig(w.T, w.d_model, w.d_ff, w.E, w.k, w.G, w.capacity_factor, rr.RR_BF16, rr.RR_ACT_SWIGLU,
+                          modes[m])
+        tables = rr.alloc_tables(cfg)
+        ws = rr.alloc_workspace(cfg)
+
+        def step():
+            rr.rr_moe_forward(cfg, dev["x"], dev["w_router"], dev["bias"], dev["w1"], dev["w3"], dev["w2"], out,
+                              tables, logits, ws)
+
+        for _ in range(warmup):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        th = tables.to_host()
+        rows.append({"k": k, "capacity_factor": cf, "experts_per_gpu": w.E // G, "mode": m, "ms_per_step": round(ms, 4),
+                     "tokens_per_s": round(w.T / (ms * 1e-3)),
+                     "slot_rows": int(th["fill_total"].sum()), "ir_rows": int(th["ir_offset"][-1]),
+                     "dropped_assignments": int((th["slot"][:, :k] < 0).sum()),
+                     "unprocessed_tokens": int((th["combine_w"].sum(axis=1) == 0).sum())})
+        del tables, ws
+    return {"metric": "rectified_moe_layer_tokens_per_s_vs_capacity_factor", "unit": "tokens/s", "n_gpus": 1,
+            "steps": steps, "warmup": warmup, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": "c3 shape: T=%d d=%d F=%d E=%d, SwiGLU" % (base.T, base.d_model, base.d_ff, base.E)},
+            "points": rows}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -144,10 +258,24 @@ def main():
     import paper_2402_12399_amd as rr
     from paper_2402_12399_amd import workloads as wl
 
+    if args.probes:
+        torch.cuda.set_device(0)
+        print(json.dumps(probes(torch)))
+        return 0
+    if args.cf_sweep:
+        torch.cuda.set_device(0)
+        print(json.dumps(cf_sweep(rr, wl, torch, min(args.steps, 20), min(args.warmup, 3))))
+        return 0
+
     w = wl.ALL[args.workload]
-    if w.d_ff == 0:
-        print("bench.py: workload has no expert FFN; use a forward workload", file=sys.stderr)
-        return 2
+    if w.d_ff == 0:  # the routing-only workload on its own
+        torch.cuda.set_device(0)
+        st = routing_stress(rr, wl, torch, args.steps, args.warmup)
+        print(json.dumps({"metric": "routing_rectify_mtokens_per_s", "value": st["mtokens_per_s"], "unit": "Mtokens/s",
+                          "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": st["ms_per_step"],
+                          "higher_is_better": True, "dtype": "f32", "data": "synthetic",
+                          "config": {"workload": w.name}, "roofline": st["router_roofline"], "routing_stress": st}))
+        return 0
     mode = () if args.mode == "vanilla" else tuple(args.mode.split("+"))
     torch.cuda.set_device(0)
     res = run_forward(rr, wl, torch, w, mode, args.steps, args.warmup)
@@ -229,11 +357,23 @@ def routing_stress(rr, wl, torch, steps, warmup):
     prof = rr.rr_profile_read()
     rr.rr_profile_enable(False)
     kernels = {n: v / max(c, 1) for n, (c, v) in prof.items() if c > 0}
-    # algorithmic HBM bytes per launch of the router kernel: x once, logits once, router weights once
-    router_bytes = w.T * w.d_model * 4 + w.T * w.E * 4 + w.E * w.d_model * 4
+    # algorithmic HBM bytes per launch of the router kernel: x once, logits once, router weights once,
+    # plus what its ranking epilogue writes (ranks, score keys, best local expert, per-block counts)
+    n_ir = int(tables.to_host()["ir_offset"][-1])
+    NR = w.k + 1
+    hbm = dispatch_bytes(w.T, w.E, w.k, NR, tables.capacity, n_ir)
+    router_bytes = w.T * w.d_model * 4 + w.T * w.E * 4 + w.E * w.d_model * 4 + hbm.pop("topk_rank") - 4 * w.T * w.E
     gbs = router_bytes / (kernels["router_scores"] * 1e-3) / 1e9
+    disp = [n for n in kernels if n != "router_scores"]
+    disp_ms = sum(kernels[n] for n in disp)
+    disp_bytes = sum(hbm.get(n, 0) for n in disp)
     return {"workload": w.name, "ms_per_step": ms, "mtokens_per_s": w.T / (ms * 1e-3) / 1e6,
             "kernel_ms": {n: round(v, 5) for n, v in kernels.items()},
+            "kernel_roofline": hbm_rooflines(kernels, hbm),
+            "dispatch_roofline": {"bound": "hbm", "achieved": round(disp_bytes / (disp_ms * 1e-3) / 1e9, 1),
+                                  "unit": "GB/s", "frac": round(disp_bytes / (disp_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                                  "bytes": disp_bytes, "ms": round(disp_ms, 5),
+                                  "kernels": "every kernel after the router"},
             "router_roofline": {"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                 "frac": gbs / PEAK_HBM_GBS, "bytes_per_launch": router_bytes}}
 

@@ -189,12 +189,16 @@ __global__ __launch_bounds__(64) void plan_rounds_kernel(DispatchArgs A, const i
     }
     fill_total[j] = fill;
   }
-  if (j < A.NR) {
-    int base = j * A.T;  // every token is a candidate of exactly one list per round
-    for (int e = 0; e < A.E; ++e) {
-      cat_base[j * A.E + e] = base;
-      base += cat_cnt[j * A.E + e];
+  // every token is a candidate of exactly one list per round: round r's lists tile [r T, (r+1) T)
+  for (int r = 0; r < A.NR; ++r) {
+    const int c = j < A.E ? cat_cnt[r * A.E + j] : 0;
+    int incl = c;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      int t = __shfl_up(incl, off);
+      if (j >= off) incl += t;
     }
+    if (j < A.E) cat_base[r * A.E + j] = r * A.T + incl - c;
   }
 }
 

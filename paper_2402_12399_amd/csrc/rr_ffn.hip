@@ -153,11 +153,21 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
   // in the shadow of the K loop (whose next barrier is a whole K chunk of MFMAs away) and are only
   // touched after it, so no tile ever waits for a table lookup.
   struct Info { int e, m0, rbase, rows_e, fill_e, iroff_e, n0; };
+  // Load addressing.  Instruction i of wave w fills stage rows [8 q, 8 q + 8), q = i * NW + w: lane l
+  // fetches row 8 q + l / 8.  The swizzle of that row, ((8 q + l / 8) >> 1) & 7, does not depend on i
+  // (8 NW is a multiple of 16), so a lane's offsets into one operand differ by a wave-uniform row
+  // step from one instruction to the next: one register per operand (A gathered: one per
+  // instruction), the step added when the load is issued.
+  static_assert((8 * NW) % 16 == 0, "swizzle must not depend on the instruction index");
+  constexpr int NVA = GATHER ? NIA : 1;
   struct Tile {
     int e, m0, rbase, rows_e, n0, live;
-    int voff[NI];
+    int va[NVA], vb;
     __amdgpu_buffer_rsrc_t rsA, rsB0, rsB1;
   };
+  const int lrow = w * 8 + (lane >> 3);            // stage row of this lane in instruction 0
+  const int lcol = ((lane & 7) ^ swz(lrow)) * 16;  // byte position of its 16-byte chunk in the global row
+  const int rstep = NW * 8 * K * 2;                // bytes between the rows of consecutive instructions
   const char *Ab = static_cast<const char *>(P.A);
   auto raw_load = [&](int Lt, int4 &ra, int4 &rb) {
     const int4 *q = reinterpret_cast<const int4 *>(P.tiles + Lt / NT);
@@ -198,22 +208,13 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
                                                 (int)min((size_t)f.rows_e * K * 2, (size_t)0x7fffffff), BUF_FLAGS);
     t.rsB0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(B0b), 0, N * K * 2, BUF_FLAGS);
     t.rsB1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(B1b), 0, N * K * 2, BUF_FLAGS);
-    // instruction i of wave w fills stage rows [8 q, 8 q + 8), q = i * NW + w
+    if (GATHER) {
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      const int r = (i * NW + w) * 8 + (lane >> 3);
-      const int c = (lane & 7) ^ swz(r);
-      if (i < NIA) {
-        if (GATHER)
-          t.voff[i] = tok[i < NIA ? i : 0] >= 0 ? tok[i < NIA ? i : 0] * K * 2 + c * 16 : 0x7ffffff0;  // past the range: zero
-        else
-          t.voff[i] = (f.m0 + r) * K * 2 + c * 16;
-      } else {
-        int nr = r - BM;
-        if (GATED && nr >= BN) nr -= BN;
-        t.voff[i] = (f.n0 + nr) * K * 2 + c * 16;
-      }
+      for (int i = 0; i < NVA; ++i) t.va[i] = tok[i] >= 0 ? tok[i] * K * 2 + lcol : 0x7ffffff0;  // past the range: zero
+    } else {
+      t.va[0] = (f.m0 + lrow) * K * 2 + lcol;
     }
+    t.vb = (f.n0 + lrow) * K * 2 + lcol;  // gate and up rows (GATED) sit at the same offsets of W1 and W3
   };
   auto issue_loads = [&](const Tile &t, int kt, int stage) {
     char *st = smem + stage * PK_STAGE + w * 1024;
@@ -223,11 +224,12 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
       // which operand instruction i reads is known at compile time
       auto lp = (__attribute__((address_space(3))) void *)(st + i * NW * 1024);
       if (i < NIA)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(t.rsA, lp, 16, t.voff[i], koff, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(t.rsA, lp, 16, GATHER ? t.va[i < NVA ? i : 0] : t.va[0] + i * rstep, koff,
+                                                 0, 0);
       else if (!GATED || i < NIA + NIB0)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(t.rsB0, lp, 16, t.voff[i], koff, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(t.rsB0, lp, 16, t.vb + (i - NIA) * rstep, koff, 0, 0);
       else
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(t.rsB1, lp, 16, t.voff[i], koff, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(t.rsB1, lp, 16, t.vb + (i - NIA - NIB0) * rstep, koff, 0, 0);
     }
   };
 
