@@ -42,6 +42,16 @@ __device__ inline u32 f32_to_bf16_bits(float f) {
 }
 
 __device__ inline float silu(float g) { return g / (1.0f + __expf(-g)); }
+// for results that are rounded to bf16 right away: hardware reciprocal (1 ulp) instead of a division
+__device__ inline float silu_fast(float g) { return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)); }
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+// two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32), first value in the low half
+__device__ inline u32 pack_bf16(float a, float b) {
+  const f32x2_t f = {a, b};
+  return __builtin_bit_cast(u32, __builtin_convertvector(f, bf16x2_t));
+}
 __device__ inline float gelu_erf(float g) { return 0.5f * g * (1.0f + erff(g * 0.70710678118654752f)); }
 
 constexpr int GB_BK = 64;             // bf16 elements per K chunk = 128 B per LDS row
@@ -92,14 +102,51 @@ __device__ inline void store_tile(f32x16 (&acc)[WM][WN], uint16_t *Cb, int rbase
   }
 }
 
+// Epilogue of the persistent kernel, which multiplies with the operands swapped (B fragment first):
+// the 32x32 accumulator then holds the transposed tile, i.e. a lane owns ONE output row (lane % 32
+// of the A fragment) and, per fragment, four groups of four consecutive columns
+// (8 * (v / 4) + 4 * (lane / 32) + v % 4): four 8-byte stores per fragment instead of sixteen
+// 2-byte ones.
+template <int WM, int WN, bool GATED, int ACT>
+__device__ inline void store_tile_t(f32x16 (&acc)[WM][WN], uint16_t *Cb, int rbase, int rows_e, int m0, int n0, int N,
+                                    int wm, int wn, int lane) {
+  constexpr int NJ = GATED ? WN / 2 : WN;  // output column fragments per wave
+  const int fr = lane & 31, fh = lane >> 5;
+  const int wrow0 = m0 + wm * WM * 32, wcol0 = n0 + wn * NJ * 32;
+  const bool cols_in = wcol0 + NJ * 32 <= N;  // N % 8 == 0: a group of four columns is inside or outside as a whole
+#pragma unroll
+  for (int i = 0; i < WM; ++i) {
+    const int row = wrow0 + i * 32 + fr;
+    if (row >= rows_e) continue;
+    uint16_t *prow = Cb + (size_t)(rbase + row) * N + wcol0 + 4 * fh;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float c[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          c[u] = acc[i][j][4 * g + u];
+          if (GATED) c[u] = silu_fast(c[u]) * acc[i][j + NJ][4 * g + u];
+          if (ACT == RR_ACT_GELU) c[u] = gelu_erf(c[u]);
+        }
+        if (cols_in || wcol0 + j * 32 + 8 * g + 4 * fh < N)
+          *reinterpret_cast<uint2 *>(prow + j * 32 + 8 * g) = make_uint2(pack_bf16(c[0], c[1]), pack_bf16(c[2], c[3]));
+      }
+    }
+  }
+}
+
 __device__ inline int swz(int r) { return (r >> 1) & 7; }
 
-// Barrier that publishes LDS-DMA data: the wave's own buffer_load ... lds must have written LDS
-// (vmcnt 0) before it signals.  The compiler's barrier only orders what its memory model knows to
-// be LDS traffic (lgkmcnt), so the wait is spelled out.
+// Barrier that publishes LDS-DMA data.  Before it signals, a wave's own buffer_load ... lds must
+// have written LDS - all of them but the youngest YOUNGER, which belong to a later chunk (memory
+// instructions complete in order) - and its own fragment reads of the stage that is about to be
+// refilled must have returned (lgkmcnt 0).  Spelled out in assembly: the compiler's barrier waits
+// for what its memory model takes for LDS traffic only, and when it does drain vmcnt it drains all.
+template <int YOUNGER>
 __device__ inline void dma_barrier() {
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-  __syncthreads();
+  asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(YOUNGER) : "memory");
 }
 
 // ------------------------------------------------------------------ bf16, persistent, LDS DMA
@@ -108,8 +155,12 @@ constexpr int PK_NW = PK_WAVES_M * PK_WAVES_N;
 constexpr int PK_THREADS = PK_NW * 64;
 constexpr int PK_BM = PK_WAVES_M * PK_WM * 32;     // 256
 constexpr int PK_BROWS = PK_WAVES_N * PK_WN * 32;  // 256 staged B rows
-constexpr int PK_STAGE = (PK_BM + PK_BROWS) * GB_ROW_BYTES;
+constexpr int PK_STAGE = (PK_BM + PK_BROWS) * GB_ROW_BYTES;  // one K chunk of A and B (the register-staged kernel)
 constexpr int PK_LDS = 2 * PK_STAGE;
+constexpr int PK_A_STAGE = PK_BM * GB_ROW_BYTES, PK_B_STAGE = PK_BROWS * GB_ROW_BYTES;
+constexpr int PK_A_STAGES = 2, PK_B_STAGES = 3;
+constexpr int PK_B_BASE = PK_A_STAGES * PK_A_STAGE;
+constexpr int PK_SMEM = PK_B_BASE + PK_B_STAGES * PK_B_STAGE;  // 160 KB: all of a CU's LDS
 constexpr int PK_NI = (PK_BM + PK_BROWS) / 8 / PK_NW;  // 1 KB load instructions per wave per chunk
 constexpr int PK_NIA = PK_BM / 8 / PK_NW;
 
@@ -123,9 +174,40 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
   extern __shared__ __attribute__((aligned(16))) char smem[];
 
   const int K = P.K, N = P.N, NT = P.NT, KT = K / GB_BK;
-  const int total = P.ctl[0] * NT;
-  int L = blockIdx.x;
-  if (L >= total) return;
+  // Tile order.  Workgroups are dealt to the 8 XCDs round-robin (workgroup g runs on XCD g % 8) and
+  // each XCD has its own L2.  In every round the workgroups of one XCD take a panel of pm x pn
+  // neighbouring tiles (4 row tiles x 8 column tiles for 32 workgroups per XCD): a chunk of an A row
+  // tile is then fetched into that L2 once for pn tiles and a chunk of a B column tile once for pm,
+  // instead of once per tile.  Panels are numbered column-panel first, so consecutive rounds of an
+  // XCD stay on the same rows of the same expert.  Slots of a panel that fall outside the tile grid
+  // are skipped.
+  const int MT = P.ctl[0];
+  const int G = gridDim.x;
+  const int nX = (G & 7) == 0 ? 8 : 1, S = G / nX;
+  const int pn = (S & 7) == 0 ? 8 : 1, pm = S / pn;
+  const int xcd = blockIdx.x % nX, slot = blockIdx.x / nX, dm = slot / pn, dn = slot - dm * pn;
+  const int PN = (NT + pn - 1) / pn, npanels = PN * ((MT + pm - 1) / pm);
+  // this workgroup's first tile at or after round i: its linear index mt * NT + nt in Lt (-1: none)
+  auto seek = [&](int i, int &Lt) {
+    for (;; ++i) {
+      const int q = i * nX + xcd;
+      if (q >= npanels) {
+        Lt = -1;
+        return i;
+      }
+      const int qm = q / PN, qn = q - qm * PN, mt = qm * pm + dm, nt = qn * pn + dn;
+      if (mt < MT && nt < NT) {
+        Lt = mt * NT + nt;
+        return i;
+      }
+    }
+  };
+  int L, L1, L2;  // this workgroup's current tile and the two after it
+  int rnd = seek(0, L);
+  if (L < 0) return;
+  rnd = seek(rnd + 1, L1);
+  L2 = -1;
+  if (L1 >= 0) rnd = seek(rnd + 1, L2);
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS-DMA addressing scalar
   const int wm = w / PK_WAVES_N, wn = w % PK_WAVES_N;
@@ -145,7 +227,7 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
     } else {
       r = (wn * WN + j) * 32 + fr;
     }
-    b_off[j] = (BM + r) * GB_ROW_BYTES;
+    b_off[j] = r * GB_ROW_BYTES;
   }
 
   // per-tile state.  A tile's table entry is fetched two tiles ahead and (GATHER) its token indices
@@ -160,10 +242,21 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
   // instruction), the step added when the load is issued.
   static_assert((8 * NW) % 16 == 0, "swizzle must not depend on the instruction index");
   constexpr int NVA = GATHER ? NIA : 1;
+  // A tile keeps the base and range of its operands; the buffer descriptors are put together from
+  // them when loads are issued, through readfirstlane: a descriptor that the register allocator has
+  // parked in vector registers would otherwise be treated as divergent and every load wrapped in a
+  // waterfall loop.
   struct Tile {
     int e, m0, rbase, rows_e, n0, live;
     int va[NVA], vb;
-    __amdgpu_buffer_rsrc_t rsA, rsB0, rsB1;
+    unsigned long long pa, pb0, pb1;
+    int na;
+  };
+  auto rsrc_of = [](unsigned long long base, int range) {
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)base);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)(base >> 32));
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<char *>(((unsigned long long)hi << 32) | lo), 0,
+                                             __builtin_amdgcn_readfirstlane(range), BUF_FLAGS);
   };
   const int lrow = w * 8 + (lane >> 3);            // stage row of this lane in instruction 0
   const int lcol = ((lane & 7) ^ swz(lrow)) * 16;  // byte position of its 16-byte chunk in the global row
@@ -187,13 +280,16 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
   };
   // the dispatch gather (Sec. 3: tokens travel to their experts): the tokens behind this lane's A
   // rows - occupied capacity slots first, then the expert's Intra-GPU rows; -1 = padding
+  // Every lane always loads (rows past the expert's end read a valid dummy and are masked when the
+  // offsets are built): the number of memory instructions per tile is then fixed, which the counted
+  // waits of the K loop rely on.
   auto lookup_tokens = [&](const Info &f, int (&tok)[NIA]) {
 #pragma unroll
     for (int i = 0; i < NIA; ++i) {
       const int lr = f.m0 + (i * NW + w) * 8 + (lane >> 3);  // row within the expert
-      tok[i] = -1;
-      if (lr < f.fill_e) tok[i] = P.slot_token[(size_t)f.e * P.C + lr];
-      else if (lr < f.rows_e) tok[i] = P.ir_token[f.iroff_e + lr - f.fill_e];
+      const int32_t *src = lr < f.fill_e ? P.slot_token + ((size_t)f.e * P.C + lr) : P.ir_token + (f.iroff_e + lr - f.fill_e);
+      if (lr >= f.rows_e) src = P.slot_token;
+      tok[i] = *src;
     }
   };
   auto make_tile = [&](const Info &f, const int (&tok)[NIA], Tile &t) {
@@ -201,45 +297,67 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
     t.live = min(WM, max(0, (f.rows_e - f.m0 - wm * WM * 32 + 31) >> 5));
     const char *B0b = static_cast<const char *>(P.B0) + (size_t)f.e * N * K * 2;
     const char *B1b = GATED ? static_cast<const char *>(P.B1) + (size_t)f.e * N * K * 2 : B0b;
-    if (GATHER)
-      t.rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(Ab), 0, (int)P.a_bytes, BUF_FLAGS);
-    else
-      t.rsA = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(Ab + (size_t)f.rbase * K * 2), 0,
-                                                (int)min((size_t)f.rows_e * K * 2, (size_t)0x7fffffff), BUF_FLAGS);
-    t.rsB0 = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(B0b), 0, N * K * 2, BUF_FLAGS);
-    t.rsB1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(B1b), 0, N * K * 2, BUF_FLAGS);
+    if (GATHER) {
+      t.pa = reinterpret_cast<unsigned long long>(Ab);
+      t.na = (int)P.a_bytes;
+    } else {
+      t.pa = reinterpret_cast<unsigned long long>(Ab + (size_t)f.rbase * K * 2);
+      t.na = (int)min((size_t)f.rows_e * K * 2, (size_t)0x7fffffff);
+    }
+    t.pb0 = reinterpret_cast<unsigned long long>(B0b);
+    t.pb1 = reinterpret_cast<unsigned long long>(B1b);
     if (GATHER) {
 #pragma unroll
-      for (int i = 0; i < NVA; ++i) t.va[i] = tok[i] >= 0 ? tok[i] * K * 2 + lcol : 0x7ffffff0;  // past the range: zero
+      for (int i = 0; i < NVA; ++i) {
+        const bool real = f.m0 + (i * NW + w) * 8 + (lane >> 3) < f.rows_e && tok[i] >= 0;
+        t.va[i] = real ? tok[i] * K * 2 + lcol : 0x7ffffff0;  // padding: past the range, reads as zero
+      }
     } else {
       t.va[0] = (f.m0 + lrow) * K * 2 + lcol;
     }
     t.vb = (f.n0 + lrow) * K * 2 + lcol;  // gate and up rows (GATED) sit at the same offsets of W1 and W3
   };
-  auto issue_loads = [&](const Tile &t, int kt, int stage) {
-    char *st = smem + stage * PK_STAGE + w * 1024;
+  // One K chunk of A (NIA instructions per wave) or of B (NIB) into a stage of its ring.
+  constexpr int NIB = NI - NIA;
+  auto issue_a = [&](const Tile &t, int kt, int stage) {
+    char *st = smem + stage * PK_A_STAGE + w * 1024;
     const int koff = kt * (GB_BK * 2);
+    const __amdgpu_buffer_rsrc_t rsA = rsrc_of(t.pa, t.na);
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-      // which operand instruction i reads is known at compile time
+    for (int i = 0; i < NIA; ++i) {
       auto lp = (__attribute__((address_space(3))) void *)(st + i * NW * 1024);
-      if (i < NIA)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(t.rsA, lp, 16, GATHER ? t.va[i < NVA ? i : 0] : t.va[0] + i * rstep, koff,
-                                                 0, 0);
-      else if (!GATED || i < NIA + NIB0)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(t.rsB0, lp, 16, t.vb + (i - NIA) * rstep, koff, 0, 0);
-      else
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(t.rsB1, lp, 16, t.vb + (i - NIA - NIB0) * rstep, koff, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsA, lp, 16, GATHER ? t.va[i < NVA ? i : 0] : t.va[0] + i * rstep, koff, 0,
+                                               0);
     }
   };
+  auto issue_b = [&](const Tile &t, int kt, int stage) {
+    char *st = smem + PK_B_BASE + stage * PK_B_STAGE + w * 1024;
+    const int koff = kt * (GB_BK * 2);
+    const __amdgpu_buffer_rsrc_t rsB0 = rsrc_of(t.pb0, N * K * 2), rsB1 = rsrc_of(t.pb1, N * K * 2);
+#pragma unroll
+    for (int i = 0; i < NIB; ++i) {
+      // which weight matrix instruction i reads is known at compile time
+      auto lp = (__attribute__((address_space(3))) void *)(st + i * NW * 1024);
+      if (!GATED || i < NIB0)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB0, lp, 16, t.vb + i * rstep, koff, 0, 0);
+      else
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsB1, lp, 16, t.vb + (i - NIB0) * rstep, koff, 0, 0);
+    }
+  };
+  auto next_b = [](int sb) { return sb == PK_B_STAGES - 1 ? 0 : sb + 1; };
 
+  // LDS rings: A has two stages, B three (160 KB together).  The K chunks of a workgroup's tiles
+  // form one stream (chunk KT of a tile is chunk 0 of its next tile).  While chunk c is multiplied,
+  // A(c+1), B(c+1) and B(c+2) are in flight or landed: the weights, which stream from HBM, are
+  // fetched two chunks ahead, the activations (mostly L2 hits: a row tile is shared by all column
+  // tiles) one.  Each chunk issues A(c+1) and then B(c+2), so the barrier that publishes chunk c+1
+  // waits for everything but the NIB youngest loads.  KT >= 3.
   f32x16 acc[WM][WN];
   Tile cur, nxt;
-  Info info1;           // table entry of this workgroup's next tile
-  int4 ra2, rb2;        // raw table entry of the tile after next
+  Info info1{}, info2{};                              // table entries of this workgroup's next two tiles
+  int4 ra2 = make_int4(0, 0, 0, 0), rb2 = ra2;        // raw table entry of the tile after next
   int tok1[NIA];        // token indices of the next tile's A rows
-  int par = 0;          // LDS stage of the current tile's first chunk
-  const int stride = gridDim.x;  // tiles are dealt round-robin: L, L + stride, ...
+  int sa = 0, sb = 0;   // ring stages of the current chunk
   {
     int4 ra, rb;
     raw_load(L, ra, rb);
@@ -249,26 +367,34 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
     for (int i = 0; i < NIA; ++i) tok0[i] = -1;
     if (GATHER) lookup_tokens(f0, tok0);
     make_tile(f0, tok0, cur);
-    issue_loads(cur, 0, par);
-    if (L + stride < total) {
-      raw_load(L + stride, ra, rb);
-      info1 = finalize(L + stride, ra, rb);
+    if (L1 >= 0) {
+      raw_load(L1, ra, rb);
+      info1 = finalize(L1, ra, rb);
     }
+    issue_a(cur, 0, sa);
+    issue_b(cur, 0, sb);
+    issue_b(cur, 1, next_b(sb));
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIB) : "memory");  // own A(0), B(0) have landed
   }
   while (true) {
-    const bool have1 = L + stride < total, have2 = L + 2 * stride < total;
+    const bool have1 = L1 >= 0;
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
       for (int j = 0; j < WN; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    dma_barrier();  // chunk 0 has landed (own loads: vmcnt 0; everybody's: barrier)
-#pragma unroll
-    for (int i = 0; i < NIA; ++i) tok1[i] = -1;
-    if (GATHER && have1) lookup_tokens(info1, tok1);
-    if (have2) raw_load(L + 2 * stride, ra2, rb2);
-    if (KT > 1) issue_loads(cur, 1, par ^ 1);
+    // Everybody's A(0), B(0) have landed: each wave saw its own arrive before it stored the previous
+    // tile's results, so the barrier itself waits for no memory operation (the stores and B(1) may
+    // still be on their way).
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // table lookups for the tiles to come, issued before this chunk's loads so that they are older
+    // than anything a counted wait lets pass
+    if (GATHER) lookup_tokens(info1, tok1);
+    raw_load(L2 >= 0 ? L2 : L, ra2, rb2);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_a(cur, 1, sa ^ 1);
+    issue_b(cur, 2, next_b(next_b(sb)));
 
     // Ragged row tiles: the last tile of an expert is mostly padding.  A wave skips the fragment
     // loads and MFMAs of its 32-row fragments that lie wholly past the expert's last row (a
@@ -278,14 +404,14 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
     auto k_loop = [&](auto full_tag) {
       constexpr bool FULL = decltype(full_tag)::value;
       bf16x8 af[2][WM], bfr[2][WN];
-      auto load_frags = [&](const char *st, int ks, int slot) {
+      auto load_frags = [&](const char *sta, const char *stb, int ks, int slot) {
         const int pos = ((2 * ks + fh) ^ fsw) << 4;
 #pragma unroll
         for (int i = 0; i < WM; ++i)
-          if (FULL || i < live) af[slot][i] = *reinterpret_cast<const bf16x8 *>(st + a_off[i] + pos);
+          if (FULL || i < live) af[slot][i] = *reinterpret_cast<const bf16x8 *>(sta + a_off[i] + pos);
         if (FULL || live > 0) {
 #pragma unroll
-          for (int j = 0; j < WN; ++j) bfr[slot][j] = *reinterpret_cast<const bf16x8 *>(st + b_off[j] + pos);
+          for (int j = 0; j < WN; ++j) bfr[slot][j] = *reinterpret_cast<const bf16x8 *>(stb + b_off[j] + pos);
         }
       };
       auto mfma_step = [&](int slot) {
@@ -294,37 +420,60 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
           if (FULL || i < live) {
 #pragma unroll
             for (int j = 0; j < WN; ++j)
-              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[slot][i], bfr[slot][j], acc[i][j], 0, 0, 0);
+              // B fragment first: the accumulator holds the transposed tile (see store_tile_t)
+              acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
           }
       };
       // Software pipeline.  sched_barrier(0) pins the order "fragment loads of the NEXT k-step,
       // then the MFMAs of the current one", so every LDS read has a whole MFMA block to complete
-      // in.  The last k-step of a chunk runs after the barrier, in whose shadow the global loads of
-      // the chunk after next are issued.  The loop is rotated so that its body starts at the
-      // barrier (the compiler's wait counting is exact only inside one basic block).
-      auto step = [&](const char *st, int ks_next, int slot_next, int slot_now) {
-        load_frags(st, ks_next, slot_next);
+      // in.  The last k-step of a chunk runs after the barrier, in whose shadow the global loads
+      // are issued.  The loop is rotated so that its body starts at the barrier (the compiler's
+      // wait counting is exact only inside one basic block).
+      auto step = [&](const char *sta, const char *stb, int ks_next, int slot_next, int slot_now) {
+        load_frags(sta, stb, ks_next, slot_next);
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(slot_now);
         __builtin_amdgcn_sched_barrier(0);
       };
-      const char *st0 = smem + par * PK_STAGE;
-      load_frags(st0, 0, 0);
-      step(st0, 1, 1, 0);
-      step(st0, 2, 0, 1);
-      step(st0, 3, 1, 0);
+      const char *sta = smem + sa * PK_A_STAGE, *stb = smem + PK_B_BASE + sb * PK_B_STAGE;
+      load_frags(sta, stb, 0, 0);
+      step(sta, stb, 1, 1, 0);
+      step(sta, stb, 2, 0, 1);
+      step(sta, stb, 3, 1, 0);
+      // The looked-up values are consumed here, unconditionally, rather than where they are first
+      // needed: in straight-line code after the lookups the compiler's wait for them is a counted
+      // one (the A(1) and B(2) loads behind them stay in flight), and nothing it tracks is pending
+      // when the loop is entered or the tile ends - there it would drain every outstanding load
+      // and store.  Without a next tile the values are unused.
+      make_tile(info1, tok1, nxt);
+      info2 = finalize(L2 >= 0 ? L2 : L, ra2, rb2);
       for (int kt = 1; kt < KT; ++kt) {
-        // chunk kt has landed and nobody reads the other stage any more
-        dma_barrier();
-        const char *st = smem + ((par + kt) & 1) * PK_STAGE;
-        load_frags(st, 0, 0);
+        // A(kt) and B(kt) have landed - the B issued after A(kt) may still be on its way - and
+        // nobody reads the stages of chunk kt-1 any more
+        if (kt + 1 < KT || have1) dma_barrier<NIB>();
+        else dma_barrier<0>();
+        sa ^= 1;
+        sb = next_b(sb);
+        sta = smem + sa * PK_A_STAGE;
+        stb = smem + PK_B_BASE + sb * PK_B_STAGE;
+        load_frags(sta, stb, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         mfma_step(1);  // last k-step of chunk kt-1
-        if (kt + 1 < KT) issue_loads(cur, kt + 1, (par + kt + 1) & 1);
+        // the stream's next loads: the rest of this tile, then the first two chunks of the next one
+        if (kt + 2 < KT) {
+          issue_a(cur, kt + 1, sa ^ 1);
+          issue_b(cur, kt + 2, next_b(next_b(sb)));
+        } else if (kt + 2 == KT) {
+          issue_a(cur, kt + 1, sa ^ 1);
+          if (have1) issue_b(nxt, 0, next_b(next_b(sb)));
+        } else if (have1) {
+          issue_a(nxt, 0, sa ^ 1);
+          issue_b(nxt, 1, next_b(next_b(sb)));
+        }
         __builtin_amdgcn_sched_barrier(0);
-        step(st, 1, 1, 0);
-        step(st, 2, 0, 1);
-        step(st, 3, 1, 0);
+        step(sta, stb, 1, 1, 0);
+        step(sta, stb, 2, 0, 1);
+        step(sta, stb, 3, 1, 0);
       }
       mfma_step(1);
     };
@@ -333,19 +482,19 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
     else
       k_loop(std::false_type{});
 
-    // The stage that held chunk KT-2 was last read before the final barrier of the K loop: the next
-    // tile's first chunk goes there while this tile's results are stored.
-    par = (par + KT) & 1;
-    if (have1) {
-      make_tile(info1, tok1, nxt);
-      issue_loads(nxt, 0, par);
-    }
-    store_tile<WM, WN, GATED, ACT>(acc, static_cast<uint16_t *>(P.Cout), cur.rbase, cur.rows_e, cur.m0, cur.n0, N, wm, wn,
-                                   lane);
+    // own A(0), B(0) of the next tile have landed (they were issued one and two chunks ago), before
+    // the stores below join the queue of outstanding memory operations
+    if (have1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIB) : "memory");
+    sa ^= 1;
+    sb = next_b(sb);
+    store_tile_t<WM, WN, GATED, ACT>(acc, static_cast<uint16_t *>(P.Cout), cur.rbase, cur.rows_e, cur.m0, cur.n0, N, wm,
+                                     wn, lane);
     if (!have1) break;
     cur = nxt;
-    L += stride;
-    if (have2) info1 = finalize(L + stride, ra2, rb2);
+    L = L1;
+    L1 = L2;
+    if (L2 >= 0) rnd = seek(rnd + 1, L2);
+    info1 = info2;
   }
 #endif
 }
@@ -556,7 +705,7 @@ int cu_count() {
   return n;
 }
 
-bool persistent_ok(int K) { return K % GB_BK == 0; }
+bool persistent_ok(int K) { return K % GB_BK == 0 && K >= 3 * GB_BK; }  // whole K chunks, at least three
 
 }  // namespace
 
@@ -576,11 +725,11 @@ hipError_t launch_ffn_part(const Dims &D, const void *x, const rr_tables &tb, co
     const bool gated = D.act == RR_ACT_SWIGLU;
     static bool attr_done = false;
     if (!attr_done) {
-      if ((err = set_lds(gemm_bf16_persistent_kernel<true, -1, true>, PK_LDS)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_persistent_kernel<true, -1, false>, PK_LDS)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, true>, PK_LDS)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, false>, PK_LDS)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_persistent_kernel<false, -1, false>, PK_LDS)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_persistent_kernel<true, -1, true>, PK_SMEM)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_persistent_kernel<true, -1, false>, PK_SMEM)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, true>, PK_SMEM)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, false>, PK_SMEM)) != hipSuccess) return err;
+      if ((err = set_lds(gemm_bf16_persistent_kernel<false, -1, false>, PK_SMEM)) != hipSuccess) return err;
       if ((err = set_lds(gemm_bf16_staged_kernel<true, -1>, PK_LDS)) != hipSuccess) return err;
       if ((err = set_lds(gemm_bf16_staged_kernel<false, RR_ACT_GELU>, PK_LDS)) != hipSuccess) return err;
       if ((err = set_lds(gemm_bf16_staged_kernel<false, -1>, PK_LDS)) != hipSuccess) return err;
@@ -592,10 +741,10 @@ hipError_t launch_ffn_part(const Dims &D, const void *x, const rr_tables &tb, co
     if (which & 1) {
       prof_begin(K_FFN_UP, s);
       if (persistent_ok(D.d)) {
-        if (gated && fuse) gemm_bf16_persistent_kernel<true, -1, true><<<cus, PK_THREADS, PK_LDS, s>>>(up);
-        else if (gated) gemm_bf16_persistent_kernel<true, -1, false><<<cus, PK_THREADS, PK_LDS, s>>>(up);
-        else if (fuse) gemm_bf16_persistent_kernel<false, RR_ACT_GELU, true><<<cus, PK_THREADS, PK_LDS, s>>>(up);
-        else gemm_bf16_persistent_kernel<false, RR_ACT_GELU, false><<<cus, PK_THREADS, PK_LDS, s>>>(up);
+        if (gated && fuse) gemm_bf16_persistent_kernel<true, -1, true><<<cus, PK_THREADS, PK_SMEM, s>>>(up);
+        else if (gated) gemm_bf16_persistent_kernel<true, -1, false><<<cus, PK_THREADS, PK_SMEM, s>>>(up);
+        else if (fuse) gemm_bf16_persistent_kernel<false, RR_ACT_GELU, true><<<cus, PK_THREADS, PK_SMEM, s>>>(up);
+        else gemm_bf16_persistent_kernel<false, RR_ACT_GELU, false><<<cus, PK_THREADS, PK_SMEM, s>>>(up);
       } else {
         if (gated) gemm_bf16_staged_kernel<true, -1><<<up.NT * D.max_mtiles, GS_THREADS, PK_LDS, s>>>(up);
         else gemm_bf16_staged_kernel<false, RR_ACT_GELU><<<up.NT * D.max_mtiles, GS_THREADS, PK_LDS, s>>>(up);
@@ -604,7 +753,7 @@ hipError_t launch_ffn_part(const Dims &D, const void *x, const rr_tables &tb, co
     }
     if (which & 2) {
       prof_begin(K_FFN_DOWN, s);
-      if (persistent_ok(D.F)) gemm_bf16_persistent_kernel<false, -1, false><<<cus, PK_THREADS, PK_LDS, s>>>(down);
+      if (persistent_ok(D.F)) gemm_bf16_persistent_kernel<false, -1, false><<<cus, PK_THREADS, PK_SMEM, s>>>(down);
       else gemm_bf16_staged_kernel<false, -1><<<down.NT * D.max_mtiles, GS_THREADS, PK_LDS, s>>>(down);
       prof_end(K_FFN_DOWN, s);
     }
