@@ -175,39 +175,37 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
 
   const int K = P.K, N = P.N, NT = P.NT, KT = K / GB_BK;
   // Tile order.  Workgroups are dealt to the 8 XCDs round-robin (workgroup g runs on XCD g % 8) and
-  // each XCD has its own L2.  In every round the workgroups of one XCD take a panel of pm x pn
-  // neighbouring tiles (4 row tiles x 8 column tiles for 32 workgroups per XCD): a chunk of an A row
-  // tile is then fetched into that L2 once for pn tiles and a chunk of a B column tile once for pm,
-  // instead of once per tile.  Panels are numbered column-panel first, so consecutive rounds of an
-  // XCD stay on the same rows of the same expert.  Slots of a panel that fall outside the tile grid
-  // are skipped.
-  const int MT = P.ctl[0];
+  // each XCD has its own L2.  The tiles are numbered panel by panel - panels of pm x pn neighbouring
+  // tiles (4 row tiles x 8 column tiles for 32 workgroups per XCD), column panels first, ragged at the
+  // right and bottom edges of the tile grid - and each run of pm * pn consecutive numbers goes to the
+  // workgroups of one XCD: a chunk of an A row tile is then fetched into that L2 once for pn tiles
+  // and a chunk of a B column tile once for pm, instead of once per tile, and consecutive rounds of
+  // an XCD stay on the same rows of the same expert.
+  const int MT = P.ctl[0], total = MT * NT;
   const int G = gridDim.x;
   const int nX = (G & 7) == 0 ? 8 : 1, S = G / nX;
   const int pn = (S & 7) == 0 ? 8 : 1, pm = S / pn;
-  const int xcd = blockIdx.x % nX, slot = blockIdx.x / nX, dm = slot / pn, dn = slot - dm * pn;
-  const int PN = (NT + pn - 1) / pn, npanels = PN * ((MT + pm - 1) / pm);
-  // this workgroup's first tile at or after round i: its linear index mt * NT + nt in Lt (-1: none)
-  auto seek = [&](int i, int &Lt) {
-    for (;; ++i) {
-      const int q = i * nX + xcd;
-      if (q >= npanels) {
-        Lt = -1;
-        return i;
-      }
-      const int qm = q / PN, qn = q - qm * PN, mt = qm * pm + dm, nt = qn * pn + dn;
-      if (mt < MT && nt < NT) {
-        Lt = mt * NT + nt;
-        return i;
-      }
-    }
+  const int xcd = blockIdx.x % nX, slot = blockIdx.x / nX;
+  const int PMf = MT / pm, PNf = NT / pn;  // full panel rows / columns
+  // tile number k (panel order) -> linear index mt * NT + nt
+  auto tile_at = [&](int k) {
+    int qm = k / (pm * NT);
+    if (qm > PMf) qm = PMf;
+    const int r = k - qm * pm * NT, h = qm < PMf ? pm : MT - PMf * pm;
+    int qn = r / (h * pn);
+    if (qn > PNf) qn = PNf;
+    const int r2 = r - qn * h * pn, wd = qn < PNf ? pn : NT - PNf * pn;
+    const int dm = r2 / wd, dn = r2 - dm * wd;
+    return (qm * pm + dm) * NT + qn * pn + dn;
   };
-  int L, L1, L2;  // this workgroup's current tile and the two after it
-  int rnd = seek(0, L);
-  if (L < 0) return;
-  rnd = seek(rnd + 1, L1);
-  L2 = -1;
-  if (L1 >= 0) rnd = seek(rnd + 1, L2);
+  // this workgroup's i-th tile is number (i * nX + xcd) * S + slot
+  int kk = xcd * S + slot;
+  const int kstep = nX * S;
+  if (kk >= total) return;
+  int L = tile_at(kk), L1 = -1, L2 = -1;  // this workgroup's current tile and the two after it
+  if (kk + kstep < total) L1 = tile_at(kk + kstep);
+  if (kk + 2 * kstep < total) L2 = tile_at(kk + 2 * kstep);
+  kk += 2 * kstep;  // number of L2
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps LDS-DMA addressing scalar
   const int wm = w / PK_WAVES_N, wn = w % PK_WAVES_N;
@@ -493,7 +491,8 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
     cur = nxt;
     L = L1;
     L1 = L2;
-    if (L2 >= 0) rnd = seek(rnd + 1, L2);
+    kk += kstep;
+    L2 = kk < total ? tile_at(kk) : -1;
     info1 = info2;
   }
 #endif
