@@ -28,8 +28,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # written (WRITE_SIZE x 1.0), from two rocprofv3 --pmc runs of this benchmark; see
 # profiles/bench_c2_forward_hbm_traffic.md.  Keyed by (workload, kernel); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2_top1_bf16_zipf1.1", "ffn_gate_up"): 2432.5e6 + 114.7e6,
-    ("c2_top1_bf16_zipf1.1", "ffn_down"): 1468.4e6 + 41.7e6,
+    ("c2_top1_bf16_zipf1.1", "ffn_gate_up"): 1967.9e6 + 114.7e6,
+    ("c2_top1_bf16_zipf1.1", "ffn_down"): 815.1e6 + 42.1e6,
 }
 
 
