@@ -145,6 +145,13 @@ SMALL_BF16 = [
     wl.Workload("s2", 1000, 136, 264, 6, 2, 1, 0.5, "bf16", "swiglu", "zipf:1.5", 12),   # ragged everything
     wl.Workload("s3", 768, 128, 256, 4, 4, 1, 1.0, "bf16", "gelu", "normal:1.0", 13),
     wl.Workload("s4", 600, 72, 200, 4, 2, 2, 1.0, "f32", "swiglu", "normal:1.0", 14),
+    # the LDS-DMA GEMM at its shortest K (three chunks, both projections) with gathered rows
+    wl.Workload("s5", 1536, 192, 192, 4, 2, 2, 1.0, "bf16", "swiglu", "normal:0.5", 15),
+    # GELU variant of the LDS-DMA GEMM with the fused gather; d_ff not a multiple of the column tile
+    wl.Workload("s6", 1024, 256, 384, 4, 2, 1, 1.0, "bf16", "gelu", "normal:1.0", 16),
+    # more tiles than compute units at three chunks per tile (every workgroup streams from one tile
+    # into the next); the down projection's only column tile is narrower than the tile
+    wl.Workload("s7", 2048, 192, 5632, 4, 2, 1, 1.0, "bf16", "swiglu", "zipf:1.1", 17),
 ]
 
 
