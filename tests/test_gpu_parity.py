@@ -192,6 +192,19 @@ def _full_size_case(w, mode, n_sample=1024):
     return tables
 
 
+def test_forward_is_deterministic():
+    """The layer has no atomics on data and a fixed reduction order: repeated calls on the same
+    inputs must give the same bits (an LDS or load-ordering race in the grouped GEMM would not)."""
+    w = wl.C2
+    dev = wl.make_inputs_device(w)
+    cfg = gu.config_of(w, ("ir", "fr"))
+    first, _, _ = gu.run_forward(cfg, dev, want_tables=False)
+    first = first.clone()
+    for _ in range(4):
+        again, _, _ = gu.run_forward(cfg, dev, want_tables=False)
+        assert torch.equal(first.view(torch.int16), again.view(torch.int16))
+
+
 @pytest.mark.parametrize("mode", MODES, ids=["vanilla", "ir", "fr", "ir+fr"])
 def test_forward_c2_full_size(mode):
     _full_size_case(wl.C2, mode)
