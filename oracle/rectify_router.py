@@ -20,6 +20,8 @@ Each function follows one passage of the paper, in the paper's order:
                         ("first routing", "second routing")
   intra_gpu_rectification()  Sec. 4.1
   fill_in_rectification()    Sec. 4.2 (stage 1: nomination, stage 2: selection)
+  topk_capacity_rounds_quota(), fill_in_rectification_quota()
+                        the same two steps with the capacity of Sec. 3 read per GPU
   combine_weights()     Eq. 2 and Eq. 3
   expert_ffn()          Sec. 5.1 "Model": experts are LLaMA FFNs (SwiGLU)
   moe_output()          Eq. 2 / Eq. 3 applied to expert outputs
@@ -40,7 +42,13 @@ documented rule of the HIP library):
     expert that already serves, or that dropped, the token);
   * every token nominates its (k+1)-th expert for Fill-in, kept or not;
   * with both rectifications, (k - |R_i|) counts top-k drops only and a placed
-    fill-in joins the sum over R_i.
+    fill-in joins the sum over R_i;
+  * capacity competition is global by default (one queue of C slots per expert
+    over all T tokens, Fig. 1).  The variant quota=True reads the capacity
+    formula of Sec. 3 per GPU, as expert-parallel implementations do: every
+    group g owns Cq = capacity(T/G, E, capacity_factor) slots of every expert,
+    slots [g Cq, (g+1) Cq) of that expert's queue of G Cq slots, and only the
+    group's own tokens compete for them, in the top-k rounds and in Fill-in.
 
 Parity pins (tests/test_oracle_*.py): a hand-worked capacity-3 example
 (tests/golden/), brute-force subset enumeration on tiny inputs, the
@@ -203,13 +211,66 @@ def combine_weights(a, rank_expert, slot, k, n_drop, ir_expert):
     return cw
 
 
-def route(a, k, G, capacity_factor, intra_gpu=True, fill_in=True, policy=POLICY_SCORE):
-    """Logits -> every routing / rectification / dispatch table (Sec. 3, 4)."""
+# ----------------------------------------------------------------------------
+# Sec. 3 capacity read per GPU (quota variant): the rounds of topk_capacity_rounds
+# and the selection of fill_in_rectification, run for every (group, expert) pair
+# on the group's own tokens and the group's own Cq slots of the expert's queue.
+# ----------------------------------------------------------------------------
+def topk_capacity_rounds_quota(a, rank_expert, k, Cq, G, policy=POLICY_SCORE):
+    a = np.asarray(a, dtype=np.float32)
+    T, E = a.shape
+    Tg = T // G
+    slot = np.full((T, k + 1), -1, dtype=np.int32)
+    slot_token = np.full((E, G * Cq), -1, dtype=np.int32)
+    fill = np.zeros((G, E), dtype=np.int32)  # occupied slots of group g's block of expert j
+    group = np.arange(T) // Tg
+    for r in range(k):
+        for g in range(G):
+            for j in range(E):
+                cand = np.flatnonzero((rank_expert[:, r] == j) & (group == g))
+                m = min(len(cand), Cq - int(fill[g, j]))
+                kept = np.sort(_best_first(cand, a[cand, j], policy)[:m])
+                first = g * Cq + int(fill[g, j])
+                slot[kept, r] = first + np.arange(m, dtype=np.int32)
+                slot_token[j, first:first + m] = kept
+                fill[g, j] += m
+    return slot, slot_token, fill
+
+
+def fill_in_rectification_quota(a, rank_expert, k, Cq, G, slot, slot_token, fill_topk):
+    a = np.asarray(a, dtype=np.float32)
+    T, E = a.shape
+    Tg = T // G
+    slot = slot.copy()
+    slot_token = slot_token.copy()
+    fill = fill_topk.copy()
+    nominee = rank_expert[:, k]
+    group = np.arange(T) // Tg
+    for g in range(G):
+        for j in range(E):
+            cand = np.flatnonzero((nominee == j) & (group == g))
+            m = min(len(cand), Cq - int(fill_topk[g, j]))
+            chosen = np.sort(_best_first(cand, a[cand, j], POLICY_SCORE)[:m])
+            first = g * Cq + int(fill_topk[g, j])
+            slot[chosen, k] = first + np.arange(m, dtype=np.int32)
+            slot_token[j, first:first + m] = chosen
+            fill[g, j] += m
+    return slot, slot_token, fill
+
+
+def route(a, k, G, capacity_factor, intra_gpu=True, fill_in=True, policy=POLICY_SCORE, quota=False):
+    """Logits -> every routing / rectification / dispatch table (Sec. 3, 4).
+
+    quota=True: per-group capacity; C in the result is then the number of slots per expert, G Cq,
+    and fill_topk / fill_total are summed over groups (fill_topk_group / fill_total_group [G,E]
+    hold the per-group counts)."""
     a = np.asarray(a, dtype=np.float32)
     assert np.isfinite(a).all(), "logits must be finite"
     T, E = a.shape
     assert E % G == 0 and T % G == 0 and 1 <= k <= E
     assert not fill_in or k + 1 <= E
+    if quota:
+        return _route_quota(a, k, G, capacity_factor, intra_gpu, fill_in, policy)
     C = capacity(T, E, capacity_factor)
     rank_expert = rank_experts(a, k + 1)
     slot, slot_token, fill_topk = topk_capacity_rounds(a, rank_expert, k, C, policy)
@@ -230,6 +291,31 @@ def route(a, k, G, capacity_factor, intra_gpu=True, fill_in=True, policy=POLICY_
                 fill_topk=fill_topk, fill_total=fill_total, n_drop=n_drop,
                 ir_expert=ir_expert, ir_row=ir_row, ir_offset=ir_offset, ir_token=ir_token,
                 combine_w=cw)
+
+
+def _route_quota(a, k, G, capacity_factor, intra_gpu, fill_in, policy):
+    T, E = a.shape
+    Cq = capacity(T // G, E, capacity_factor)
+    rank_expert = rank_experts(a, k + 1)
+    slot, slot_token, fill_topk_g = topk_capacity_rounds_quota(a, rank_expert, k, Cq, G, policy)
+    if intra_gpu:
+        n_drop, ir_expert, ir_row, ir_offset, ir_token = intra_gpu_rectification(a, slot, k, G)
+    else:
+        n_drop = (slot[:, :k] < 0).sum(axis=1).astype(np.int32)
+        ir_expert = np.full(T, -1, dtype=np.int32)
+        ir_row = np.full(T, -1, dtype=np.int32)
+        ir_offset = np.zeros(E + 1, dtype=np.int32)
+        ir_token = np.zeros(0, dtype=np.int32)
+    if fill_in:
+        slot, slot_token, fill_total_g = fill_in_rectification_quota(a, rank_expert, k, Cq, G, slot, slot_token,
+                                                                     fill_topk_g)
+    else:
+        fill_total_g = fill_topk_g.copy()
+    cw = combine_weights(a, rank_expert, slot, k, n_drop, ir_expert)
+    return dict(C=G * Cq, Cq=Cq, rank_expert=rank_expert, slot=slot, slot_token=slot_token,
+                fill_topk=fill_topk_g.sum(axis=0).astype(np.int32), fill_total=fill_total_g.sum(axis=0).astype(np.int32),
+                fill_topk_group=fill_topk_g, fill_total_group=fill_total_g, n_drop=n_drop,
+                ir_expert=ir_expert, ir_row=ir_row, ir_offset=ir_offset, ir_token=ir_token, combine_w=cw)
 
 
 # ----------------------------------------------------------------------------

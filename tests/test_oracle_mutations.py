@@ -294,13 +294,47 @@ def m_output_ignores_intra_gpu(mp):
     mp.setattr(orc, "moe_output", out)
 
 
+def m_quota_ignores_groups(mp):
+    def rounds(a, rank_expert, k, Cq, G, policy=orc.POLICY_SCORE):  # one queue of G Cq slots for everybody
+        slot, slot_token, fill = orc.topk_capacity_rounds(a, rank_expert, k, G * Cq, policy)
+        per_group = np.zeros((G, a.shape[1]), dtype=np.int32)
+        per_group[0] = fill
+        return slot, slot_token, per_group
+    mp.setattr(orc, "topk_capacity_rounds_quota", rounds)
+
+
+def m_quota_capacity_from_all_tokens(mp):
+    real = orc._route_quota
+    mp.setattr(orc, "_route_quota", lambda a, k, G, cf, ir, fr, policy: real(a, k, G, cf * G, ir, fr, policy))
+
+
+def m_quota_fill_in_over_all_groups(mp):
+    def fr(a, rank_expert, k, Cq, G, slot, slot_token, fill_topk):  # nominees compete across groups
+        a = np.asarray(a, dtype=np.float32)
+        T, E = a.shape
+        slot, slot_token, fill = slot.copy(), slot_token.copy(), fill_topk.copy()
+        for j in range(E):
+            cand = np.flatnonzero(rank_expert[:, k] == j)
+            order = orc._best_first(cand, a[cand, j], orc.POLICY_SCORE)
+            for i in order:
+                for g in range(G):
+                    if fill[g, j] < Cq:
+                        slot[i, k] = g * Cq + fill[g, j]
+                        slot_token[j, slot[i, k]] = i
+                        fill[g, j] += 1
+                        break
+        return slot, slot_token, fill
+    mp.setattr(orc, "fill_in_rectification_quota", fr)
+
+
 MUTATIONS = [
     m_keep_lowest_scores, m_token_tie_break_reversed, m_expert_tie_break_reversed, m_capacity_floor,
     m_slots_in_score_order, m_rounds_forget_earlier_fill, m_ir_tokens_interleaved_over_groups, m_ir_ignores_groups,
     m_ir_only_when_all_choices_dropped, m_only_dropped_tokens_nominate, m_fill_in_evicts,
     m_ir_term_without_drop_count, m_weights_are_gate_probabilities, m_swiglu_gate_and_up_swapped,
     m_gelu_tanh_approximation, m_down_projection_read_in_the_wrong_layout, m_router_bias_subtracted, m_softmax_over_tokens,
-    m_output_ignores_fill_in, m_output_ignores_intra_gpu,
+    m_output_ignores_fill_in, m_output_ignores_intra_gpu, m_quota_ignores_groups, m_quota_capacity_from_all_tokens,
+    m_quota_fill_in_over_all_groups,
 ]
 
 

@@ -519,3 +519,120 @@ def test_invariants(seed):
     t2 = orc.route(a, k, G, cf, True, True, policy)
     for name in t:
         assert np.array_equal(np.asarray(t[name]), np.asarray(t2[name]))
+
+
+# ---------------------------------------------------------------- capacity read per GPU (quota variant)
+def test_quota_hand_worked_example():
+    """Four tokens, two experts, two groups of two tokens, top-1 with Fill-in, capacity factor 1:
+    Cq = ceil(1 * 2 / 2) = 1 slot per (group, expert); slot g of an expert's queue belongs to group g.
+
+    Round 0: tokens 0 and 1 (group 0) both choose expert 0; its group-0 slot takes the better one, token 1
+    (2.0 > 1.0), token 0 is dropped.  Token 2 takes expert 0's group-1 slot, token 3 expert 1's group-1 slot.
+    Fill-in: tokens 0, 1, 2 nominate expert 1, token 3 expert 0.  Expert 1's group-0 slot is vacant and goes to
+    the better group-0 nominee, token 1 (0.5 > 0.0); its group-1 slot and both slots of expert 0 are taken.
+    Intra-GPU: token 0 was dropped; group 0 hosts expert 0 only."""
+    a = np.array([[1.0, 0.0],
+                  [2.0, 0.5],
+                  [3.0, 0.0],
+                  [0.0, 1.0]], dtype=np.float32)
+    q = orc.route(a, 1, 2, 1.0, intra_gpu=True, fill_in=True, quota=True)
+    assert q["C"] == 2 and q["Cq"] == 1
+    assert q["slot_token"].tolist() == [[1, 2], [1, 3]]
+    assert q["slot"].tolist() == [[-1, -1], [0, 0], [1, -1], [1, -1]]
+    assert q["fill_topk_group"].tolist() == [[1, 0], [1, 1]] and q["fill_total_group"].tolist() == [[1, 1], [1, 1]]
+    assert q["fill_topk"].tolist() == [2, 1] and q["fill_total"].tolist() == [2, 2]
+    assert q["ir_expert"].tolist() == [0, -1, -1, -1] and q["n_drop"].tolist() == [1, 0, 0, 0]
+    # the global reading (C = 2 slots per expert for all four tokens): expert 0 keeps the two best of its three
+    # candidates, tokens 1 and 2; expert 1 keeps token 3 and fills its second slot with the best nominee, token 1
+    g = orc.route(a, 1, 2, 1.0, intra_gpu=True, fill_in=True, quota=False)
+    assert g["slot_token"].tolist() == [[1, 2], [3, 1]]
+
+
+def test_quota_with_one_group_is_the_global_reading():
+    rng = np.random.default_rng(7)
+    a = np.round(rng.standard_normal((48, 6)) * 2).astype(np.float32) / 2
+    for k in (1, 2):
+        for policy in ("score", "arrival"):
+            g = orc.route(a, k, 1, 0.75, True, True, policy, quota=False)
+            q = orc.route(a, k, 1, 0.75, True, True, policy, quota=True)
+            for name in g:
+                assert np.array_equal(np.asarray(g[name]), np.asarray(q[name])), name
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_quota_is_independent_routing_per_group(seed):
+    """Second formulation: with quotas the slotting of group g is the global slotting of the batch made of
+    group g's tokens alone, at capacity capacity(T/G, E, cf), written into the group's block of every queue."""
+    rng = np.random.default_rng(500 + seed)
+    E, G, Tg = [4, 8, 6][seed % 3], [2, 4, 3][seed % 3], [24, 16, 20][seed % 3]
+    k = 1 + seed % 2
+    cf = [0.5, 1.0, 1.5][(seed // 2) % 3]
+    policy = "arrival" if seed % 3 == 0 else "score"
+    T = G * Tg
+    a = np.round((rng.standard_normal((T, E)) + rng.standard_normal(E)) * 2).astype(np.float32) / 2
+    q = orc.route(a, k, G, cf, intra_gpu=False, fill_in=True, policy=policy, quota=True)
+    Cq = orc.capacity(Tg, E, cf)
+    assert q["Cq"] == Cq and q["C"] == G * Cq
+    slot = np.full((T, k + 1), -1, dtype=np.int64)
+    slot_token = np.full((E, G * Cq), -1, dtype=np.int64)
+    for g in range(G):
+        one = orc.route(a[g * Tg:(g + 1) * Tg], k, 1, cf, intra_gpu=False, fill_in=True, policy=policy, quota=False)
+        assert one["C"] == Cq
+        local = one["slot"].astype(np.int64)
+        slot[g * Tg:(g + 1) * Tg] = np.where(local >= 0, local + g * Cq, -1)
+        st = one["slot_token"].astype(np.int64)
+        slot_token[:, g * Cq:(g + 1) * Cq] = np.where(st >= 0, st + g * Tg, -1)
+        assert q["fill_topk_group"][g].tolist() == one["fill_topk"].tolist()
+        assert q["fill_total_group"][g].tolist() == one["fill_total"].tolist()
+    assert np.array_equal(slot, q["slot"]) and np.array_equal(slot_token, q["slot_token"])
+    assert q["fill_total"].tolist() == q["fill_total_group"].sum(axis=0).tolist()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_quota_brute_force_and_invariants(seed):
+    rng = np.random.default_rng(700 + seed)
+    T, E, G = 12, 4, 2
+    Tg, Eg = T // G, E // G
+    k = 1 + seed % 2
+    cf = [0.5, 1.0, 1.5][seed % 3]
+    policy = "arrival" if seed % 2 else "score"
+    a = np.round(rng.standard_normal((T, E)) * 1.5).astype(np.float32) / 2
+    t = orc.route(a, k, G, cf, intra_gpu=True, fill_in=True, policy=policy, quota=True)
+    Cq = t["Cq"]
+    rank_expert, slot, st = t["rank_expert"], t["slot"], t["slot_token"]
+    # every (group, expert) pair by definition: the unique best subset of the group's own candidates
+    fill = [[0] * E for _ in range(G)]
+    for r in range(k + 1):
+        by_score = policy == "score" or r == k
+        for g in range(G):
+            choice = np.where(np.arange(T) // Tg == g, rank_expert[:, r], -1)  # other groups do not compete
+            kept_of = _brute_round(a, choice, fill[g], Cq, by_score=by_score)
+            for j, kept in kept_of.items():
+                for p, i in enumerate(kept):
+                    assert slot[i, r] == g * Cq + fill[g][j] + p
+                    assert st[j, slot[i, r]] == i
+                for i in np.flatnonzero(choice == j):
+                    if i not in kept:
+                        assert slot[i, r] == -1
+                fill[g][j] += len(kept)
+        if r == k - 1:
+            assert t["fill_topk_group"].tolist() == fill
+    assert t["fill_total_group"].tolist() == fill
+    # a slot of group g's block holds a token of group g or nothing; occupied slots are a prefix of the block
+    for j in range(E):
+        for g in range(G):
+            block = st[j, g * Cq:(g + 1) * Cq]
+            n = fill[g][j]
+            assert (block[:n] >= 0).all() and (block[n:] == -1).all()
+            assert all(i // Tg == g for i in block[:n])
+    # Intra-GPU Rectification is unchanged: tokens with a top-k drop, best expert of their own group
+    for i in range(T):
+        n = int((slot[i, :k] < 0).sum())
+        if n == 0:
+            assert t["ir_expert"][i] == -1
+        else:
+            local = list(range((i // Tg) * Eg, (i // Tg + 1) * Eg))
+            best = max(local, key=lambda j: (a[i, j], -j))
+            assert t["ir_expert"][i] == best
+    sums = t["combine_w"].sum(axis=1)
+    assert np.all(np.abs(sums - 1) < 1e-14)
