@@ -19,8 +19,8 @@
  *     validated on the host before anything is launched; no call aborts or throws.
  *   - Matrices are dense, row-major, without padding.  int32 tables use -1 for "none".
  *   - Logits must be finite; behaviour for NaN/Inf logits is undefined.
- *   - Limits: 1 <= E <= 64, 1 <= k <= 4, T <= 2^24, d_model % 8 == 0, d_ff % 8 == 0;
- *     outside them calls return RR_ERR_UNSUPPORTED.
+ *   - Limits: 1 <= E <= 64, 1 <= k <= 4, T <= 2^24, d_model % 8 == 0, d_ff % 8 == 0, and with
+ *     RR_QUOTA_PER_GROUP (T/G) % 128 == 0; outside them calls return RR_ERR_UNSUPPORTED.
  */
 #ifndef RR_H
 #define RR_H
@@ -45,10 +45,16 @@ enum { RR_ACT_GELU = 0, RR_ACT_SWIGLU = 1 };  /* rr_config.act   */
 enum {                                        /* rr_config.flags */
   RR_INTRA_GPU      = 1u, /* Sec. 4.1: re-route every dropped token inside its own group          */
   RR_FILL_IN        = 2u, /* Sec. 4.2: fill padding slots with the best (k+1)-th-choice tokens     */
-  RR_POLICY_ARRIVAL = 4u  /* overflowing experts keep the EARLIEST tokens instead of the
+  RR_POLICY_ARRIVAL = 4u, /* overflowing experts keep the EARLIEST tokens instead of the
                              highest-scoring ones (Sec. 3 says lowest scores are dropped; the
                              queue picture of Fig. 1 suggests arrival order).  Fill-in always
                              selects by score (Sec. 4.2).                                          */
+  RR_QUOTA_PER_GROUP = 8u /* the capacity formula of Sec. 3 read per GPU, as expert-parallel
+                             implementations do: every group g owns Cq = rr_capacity(T/G, E, cf)
+                             slots of every expert - slots [g Cq, (g+1) Cq) of a queue of G Cq -
+                             and only its own tokens compete for them, in the top-k rounds and
+                             in Fill-in.  Default: one queue of C slots per expert for all T
+                             tokens (Fig. 1).  Requires (T/G) % 128 == 0.                         */
 };
 
 /* Problem statement of Sec. 3: T tokens, E experts with router embeddings, top-k, capacity factor,
@@ -63,20 +69,21 @@ typedef struct rr_config {
   float    capacity_factor; /* capacity C = rr_capacity(T, E, capacity_factor)                    */
   int32_t  dtype;           /* RR_F32 | RR_BF16: type of x, expert weights and out; router fp32   */
   int32_t  act;             /* RR_ACT_SWIGLU: W2 (silu(W1 x) * (W3 x)); RR_ACT_GELU: W2 gelu(W1 x) */
-  uint32_t flags;           /* RR_INTRA_GPU | RR_FILL_IN | RR_POLICY_ARRIVAL                      */
+  uint32_t flags;           /* RR_INTRA_GPU | RR_FILL_IN | RR_POLICY_ARRIVAL | RR_QUOTA_PER_GROUP */
 } rr_config;
 
 /* Routing, rectification and dispatch tables.  All device pointers, caller-allocated, every one
- * required.  C = rr_capacity(...).  Column r < k of the [T,k+1] tables is the token's r-th choice
+ * required.  C = rr_slots_per_expert(cfg): rr_capacity(T, E, cf), or G Cq with RR_QUOTA_PER_GROUP.  Column r < k of the [T,k+1] tables is the token's r-th choice
  * (Eq. 1), column k its (k+1)-th choice, the Fill-in nomination (Sec. 4.2 stage 1; -1 if k == E). */
 typedef struct rr_tables {
   int32_t *rank_expert; /* [T,k+1] experts by descending score, ties -> lower expert index         */
   int32_t *slot;        /* [T,k+1] slot in that expert's queue, -1 = dropped / not filled in       */
   int32_t *slot_token;  /* [E,C]   token in each capacity slot, -1 = padding.  Kept tokens of a
                                    round take consecutive slots in ascending token index; rounds
-                                   0..k-1 first, Fill-in last                                      */
-  int32_t *fill_topk;   /* [E]     occupied slots after the k top-k rounds                         */
-  int32_t *fill_total;  /* [E]     occupied slots after Fill-in                                    */
+                                   0..k-1 first, Fill-in last (with quotas: inside each group's
+                                   block of Cq slots)                                              */
+  int32_t *fill_topk;   /* [E]     occupied slots after the k top-k rounds (all groups together)   */
+  int32_t *fill_total;  /* [E]     occupied slots after Fill-in (all groups together)              */
   int32_t *ir_expert;   /* [T]     Intra-GPU expert h_i of a token dropped >= once, else -1        */
   int32_t *ir_row;      /* [T]     position of the token in ir_expert's Intra-GPU list, else -1    */
   int32_t *ir_offset;   /* [E+1]   CSR offsets of the per-expert Intra-GPU lists in ir_token       */
@@ -90,6 +97,10 @@ typedef struct rr_tables {
 /* Sec. 3: capacity = capacity factor x tokens / experts, rounded up, at least 1.
  * Evaluated as ceil((double)cf * T / E).  Host function; returns -1 on invalid arguments. */
 int32_t rr_capacity(int32_t T, int32_t E, float capacity_factor);
+
+/* Slots in an expert's queue = row length of rr_tables.slot_token: rr_capacity(T, E, cf), or
+ * G * rr_capacity(T/G, E, cf) with RR_QUOTA_PER_GROUP.  Host function; -1 on invalid arguments. */
+int32_t rr_slots_per_expert(const rr_config *cfg);
 
 /* Bytes of scratch that rr_rectified_dispatch and rr_moe_forward need for this configuration
  * (the larger of the two; a multiple of 256).  Host function. */

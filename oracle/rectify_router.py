@@ -365,8 +365,8 @@ def moe_output(x, tables, k, w1, w3, w2, act, tokens=None):
 
 
 def moe_forward(x, w_router, bias, w1, w3, w2, k, G, capacity_factor, act,
-                intra_gpu=True, fill_in=True, policy=POLICY_SCORE, tokens=None):
+                intra_gpu=True, fill_in=True, policy=POLICY_SCORE, tokens=None, quota=False):
     a = router_scores(x, w_router, bias)
-    tables = route(a, k, G, capacity_factor, intra_gpu, fill_in, policy)
+    tables = route(a, k, G, capacity_factor, intra_gpu, fill_in, policy, quota)
     out = moe_output(x, tables, k, w1, w3, w2, act, tokens)
     return a, tables, out

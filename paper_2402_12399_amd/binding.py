@@ -11,7 +11,7 @@ from dataclasses import dataclass
 
 RR_F32, RR_BF16 = 0, 1
 RR_ACT_GELU, RR_ACT_SWIGLU = 0, 1
-RR_INTRA_GPU, RR_FILL_IN, RR_POLICY_ARRIVAL = 1, 2, 4
+RR_INTRA_GPU, RR_FILL_IN, RR_POLICY_ARRIVAL, RR_QUOTA_PER_GROUP = 1, 2, 4, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -73,6 +73,8 @@ def load_library():
     vp, i32, sz = C.c_void_p, C.c_int32, C.c_size_t
     lib.rr_capacity.restype = i32
     lib.rr_capacity.argtypes = [i32, i32, C.c_float]
+    lib.rr_slots_per_expert.restype = i32
+    lib.rr_slots_per_expert.argtypes = [C.POINTER(_Config)]
     lib.rr_workspace_bytes.restype = C.c_int
     lib.rr_workspace_bytes.argtypes = [C.POINTER(_Config), C.POINTER(sz)]
     lib.rr_router_scores.restype = C.c_int
@@ -113,6 +115,14 @@ def rr_capacity(T: int, E: int, capacity_factor: float) -> int:
     return int(load_library().rr_capacity(T, E, capacity_factor))
 
 
+def rr_slots_per_expert(cfg: RRConfig) -> int:
+    cc = cfg.c()
+    n = int(load_library().rr_slots_per_expert(C.byref(cc)))
+    if n < 0:
+        raise RRError("rr_slots_per_expert: invalid or unsupported configuration")
+    return n
+
+
 def rr_workspace_bytes(cfg: RRConfig) -> int:
     n = C.c_size_t(0)
     cc = cfg.c()
@@ -130,7 +140,7 @@ class Tables:
 
     def __init__(self, cfg: RRConfig, device="cuda"):
         import torch
-        C_ = rr_capacity(cfg.T, cfg.E, cfg.capacity_factor)
+        C_ = rr_slots_per_expert(cfg)
         i32 = dict(dtype=torch.int32, device=device)
         self.capacity = C_
         self.rank_expert = torch.empty((cfg.T, cfg.k + 1), **i32)

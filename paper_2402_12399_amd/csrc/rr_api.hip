@@ -54,7 +54,7 @@ static int make_dims(const rr_config *c, bool need_ffn, Dims *D) {
   if (c->E % c->G || c->T % c->G || c->k > c->E) return RR_ERR_INVALID_ARG;
   if ((c->flags & RR_FILL_IN) && c->k + 1 > c->E) return RR_ERR_INVALID_ARG;
   if (!(c->capacity_factor > 0.0f) || !isfinite(c->capacity_factor)) return RR_ERR_INVALID_ARG;
-  if (c->flags & ~(uint32_t)(RR_INTRA_GPU | RR_FILL_IN | RR_POLICY_ARRIVAL)) return RR_ERR_INVALID_ARG;
+  if (c->flags & ~(uint32_t)(RR_INTRA_GPU | RR_FILL_IN | RR_POLICY_ARRIVAL | RR_QUOTA_PER_GROUP)) return RR_ERR_INVALID_ARG;
   if (c->E > kMaxE || c->k > kMaxK || c->T > (1 << 24)) return RR_ERR_UNSUPPORTED;
   if (c->dtype != RR_F32 && c->dtype != RR_BF16) return RR_ERR_UNSUPPORTED;
   if (c->d_model % 8) return RR_ERR_UNSUPPORTED;
@@ -63,16 +63,24 @@ static int make_dims(const rr_config *c, bool need_ffn, Dims *D) {
     if (c->d_ff % 8) return RR_ERR_UNSUPPORTED;
     if (c->act != RR_ACT_GELU && c->act != RR_ACT_SWIGLU) return RR_ERR_UNSUPPORTED;
   }
-  int32_t C = rr_capacity(c->T, c->E, c->capacity_factor);
-  if (C < 1) return RR_ERR_INVALID_ARG;
-  if ((int64_t)C * c->E > ((int64_t)1 << 28)) return RR_ERR_UNSUPPORTED;
+  const int quota = (c->flags & RR_QUOTA_PER_GROUP) ? 1 : 0;
+  // token blocks of the candidate counts must not straddle groups
+  if (quota && (c->T / c->G) % kTokBlock) return RR_ERR_UNSUPPORTED;
+  const int32_t Cq = quota ? rr_capacity(c->T / c->G, c->E, c->capacity_factor)
+                           : rr_capacity(c->T, c->E, c->capacity_factor);
+  if (Cq < 1) return RR_ERR_INVALID_ARG;
+  const int Gq = quota ? c->G : 1;
+  if ((int64_t)Cq * Gq * c->E > ((int64_t)1 << 28)) return RR_ERR_UNSUPPORTED;
+  const int32_t C = Cq * Gq;
   D->T = c->T; D->d = c->d_model; D->F = c->d_ff > 0 ? c->d_ff : 0; D->E = c->E; D->k = c->k; D->G = c->G; D->C = C;
+  D->Cq = Cq; D->Gq = Gq; D->quota = quota;
   D->Eg = c->E / c->G; D->Tg = c->T / c->G;
   D->ir = (c->flags & RR_INTRA_GPU) ? 1 : 0;
   D->fr = (c->flags & RR_FILL_IN) ? 1 : 0;
   D->arrival = (c->flags & RR_POLICY_ARRIVAL) ? 1 : 0;
   D->NR = c->k + D->fr;
   D->NCAT = D->NR * c->E;
+  D->NL = D->NCAT * Gq;
   D->NB = (c->T + kTokBlock - 1) / kTokBlock;
   D->dtype = c->dtype; D->act = c->act;
   int64_t slots = (int64_t)C * c->E, assigns = (int64_t)D->NR * c->T;
@@ -103,9 +111,14 @@ static size_t carve(const Dims &D, bool forward, void *ws, Work *W) {
   W->ir_cand = cv.take<int32_t>(T);
   W->blk_cnt = cv.take<int32_t>((size_t)D.NCAT * D.NB);
   W->cat_cnt = cv.take<int32_t>(D.NCAT);
-  W->cat_m = cv.take<int32_t>(D.NCAT);
-  W->cat_fill0 = cv.take<int32_t>(D.NCAT);
   W->cat_base = cv.take<int32_t>(D.NCAT);
+  W->lst_n = cv.take<int32_t>(D.NL);
+  W->lst_m = cv.take<int32_t>(D.NL);
+  W->lst_first = cv.take<int32_t>(D.NL);
+  W->lst_base = cv.take<int32_t>(D.NL);
+  W->grp_fill = cv.take<int32_t>(E * D.Gq);
+  W->grp_off = cv.take<int32_t>(E * D.Gq);
+  W->row_token = D.quota ? cv.take<int32_t>(D.Rmax) : nullptr;
   W->cand_key = cv.take<u32>(T * NR);
   W->cand_tok = cv.take<int32_t>(T * NR);
   W->ir_blk_cnt = cv.take<int32_t>(E * D.NB);
@@ -159,6 +172,12 @@ int32_t rr_capacity(int32_t T, int32_t E, float capacity_factor) {
   if (c < 1.0) c = 1.0;
   if (c > 2147483647.0) return -1;
   return (int32_t)c;
+}
+
+int32_t rr_slots_per_expert(const rr_config *cfg) {
+  Dims D;
+  if (make_dims(cfg, false, &D) != RR_OK) return -1;
+  return D.C;
 }
 
 int rr_workspace_bytes(const rr_config *cfg, size_t *bytes) {

@@ -27,6 +27,7 @@ constexpr int TS = kMaxE + 1;  // LDS row stride of a [token][expert] tile
 
 struct DispatchArgs {
   int T, E, k, C, NR, NCAT, NB, Eg, Tg, ir, fr, arrival, BM, max_mtiles;
+  int Cq, Gq, NL;  // capacity blocks: Gq per expert (1, or one per group with per-group quotas) of Cq slots
 };
 
 // lanes of this wave whose (valid, e) equals the caller's; e < 64
@@ -171,34 +172,72 @@ __global__ __launch_bounds__(SC_THREADS) void scan_blocks_kernel(int32_t *__rest
 }
 
 // ------------------------------------------------------------------ plan_rounds
-__global__ __launch_bounds__(64) void plan_rounds_kernel(DispatchArgs A, const int32_t *__restrict__ cat_cnt,
-                                                         int32_t *__restrict__ cat_m, int32_t *__restrict__ cat_fill0,
-                                                         int32_t *__restrict__ cat_base,
-                                                         int32_t *__restrict__ fill_topk,
-                                                         int32_t *__restrict__ fill_total) {
-  const int j = threadIdx.x;
-  if (j < A.E) {
+// A selection list is the piece of a (round, expert) candidate array that competes for one capacity
+// block: the whole array and the expert's whole queue by default; with per-group quotas (Sec. 3's
+// capacity read per GPU) the candidates of group g - a contiguous piece, since candidates are in
+// ascending token index and groups are token ranges that end on block boundaries - and the group's
+// Cq slots.  Per list: candidates, kept count min(candidates, free slots of the block), first slot.
+constexpr int PL_THREADS = 1024;
+__global__ __launch_bounds__(PL_THREADS) void plan_rounds_kernel(DispatchArgs A, const int32_t *__restrict__ cat_cnt,
+                                                                 const int32_t *__restrict__ blk_off,
+                                                                 int32_t *__restrict__ cat_base,
+                                                                 int32_t *__restrict__ lst_n, int32_t *__restrict__ lst_m,
+                                                                 int32_t *__restrict__ lst_first,
+                                                                 int32_t *__restrict__ lst_base,
+                                                                 int32_t *__restrict__ grp_fill,
+                                                                 int32_t *__restrict__ grp_off,
+                                                                 int32_t *__restrict__ fill_topk,
+                                                                 int32_t *__restrict__ fill_total) {
+  __shared__ int s_base[kMaxRounds * kMaxE];
+  __shared__ int s_topk[kMaxE * kMaxE];  // occupied slots per (expert, block) after the top-k rounds
+  const int tid = threadIdx.x;
+  // every token is a candidate of exactly one array per round: round r's arrays tile [r T, (r+1) T)
+  if (tid < kWave) {
+    for (int r = 0; r < A.NR; ++r) {
+      const int c = tid < A.E ? cat_cnt[r * A.E + tid] : 0;
+      int incl = c;
+#pragma unroll
+      for (int off = 1; off < 64; off <<= 1) {
+        int t = __shfl_up(incl, off);
+        if (tid >= off) incl += t;
+      }
+      if (tid < A.E) {
+        s_base[r * A.E + tid] = r * A.T + incl - c;
+        cat_base[r * A.E + tid] = r * A.T + incl - c;
+      }
+    }
+  }
+  __syncthreads();
+  const int bpg = A.NB / A.Gq;  // token blocks per group (exact with quotas; all of them otherwise)
+  for (int p = tid; p < A.E * A.Gq; p += PL_THREADS) {
+    const int j = p / A.Gq, g = p - j * A.Gq;
     int fill = 0;
     for (int r = 0; r < A.NR; ++r) {
-      int c = r * A.E + j;
-      int m = min(cat_cnt[c], A.C - fill);
-      cat_m[c] = m;
-      cat_fill0[c] = fill;
+      const int cat = r * A.E + j;
+      const int lo = g == 0 ? 0 : blk_off[(size_t)cat * A.NB + g * bpg];
+      const int hi = g == A.Gq - 1 ? cat_cnt[cat] : blk_off[(size_t)cat * A.NB + (g + 1) * bpg];
+      const int q = cat * A.Gq + g;
+      const int m = min(hi - lo, A.Cq - fill);
+      lst_n[q] = hi - lo;
+      lst_m[q] = m;
+      lst_first[q] = g * A.Cq + fill;
+      lst_base[q] = s_base[cat] + lo;
       fill += m;
-      if (r == A.k - 1) fill_topk[j] = fill;
+      if (r == A.k - 1) s_topk[p] = fill;
     }
-    fill_total[j] = fill;
+    grp_fill[p] = fill;
   }
-  // every token is a candidate of exactly one list per round: round r's lists tile [r T, (r+1) T)
-  for (int r = 0; r < A.NR; ++r) {
-    const int c = j < A.E ? cat_cnt[r * A.E + j] : 0;
-    int incl = c;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      int t = __shfl_up(incl, off);
-      if (j >= off) incl += t;
+  __syncthreads();
+  __threadfence_block();
+  if (tid < A.E) {
+    int topk = 0, total = 0;
+    for (int g = 0; g < A.Gq; ++g) {
+      grp_off[tid * A.Gq + g] = total;
+      topk += s_topk[tid * A.Gq + g];
+      total += grp_fill[tid * A.Gq + g];
     }
-    if (j < A.E) cat_base[r * A.E + j] = r * A.T + incl - c;
+    fill_topk[tid] = topk;
+    fill_total[tid] = total;
   }
 }
 
@@ -295,10 +334,10 @@ __device__ inline u32 radix_select(int m, Each each, u32 *hist, u32 *s_pick, u32
   return prefix;
 }
 
-__global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A, const int32_t *__restrict__ cat_cnt,
-                                                                 const int32_t *__restrict__ cat_m,
-                                                                 const int32_t *__restrict__ cat_fill0,
-                                                                 const int32_t *__restrict__ cat_base,
+__global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A, const int32_t *__restrict__ lst_n,
+                                                                 const int32_t *__restrict__ lst_m,
+                                                                 const int32_t *__restrict__ lst_first,
+                                                                 const int32_t *__restrict__ lst_base,
                                                                  const u32 *__restrict__ cand_key,
                                                                  const int32_t *__restrict__ cand_tok,
                                                                  int32_t *__restrict__ slot,
@@ -307,10 +346,11 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
   __shared__ u32 s_pick[2];
   __shared__ int2 wtot[SS_PER][SS_WAVES];  // (kept-for-sure, equal-to-threshold) counts per (trip, wave)
   __shared__ int2 wsum[8];
-  const int cat = blockIdx.x, r = cat / A.E, j = cat - r * A.E;
-  const int n = cat_cnt[cat], m = cat_m[cat], fill0 = cat_fill0[cat];
-  const u32 *keys = cand_key + cat_base[cat];
-  const int32_t *toks = cand_tok + cat_base[cat];
+  // list = (round r, expert j, capacity block g); fill0 = first slot of this round's kept tokens
+  const int lst = blockIdx.x, cat = lst / A.Gq, g = lst - cat * A.Gq, r = cat / A.E, j = cat - r * A.E;
+  const int n = lst_n[lst], m = lst_m[lst], fill0 = lst_first[lst];
+  const u32 *keys = cand_key + lst_base[lst];
+  const int32_t *toks = cand_tok + lst_base[lst];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const bool by_score = !A.arrival || r == A.k;  // the Fill-in round always selects by score (Sec. 4.2)
   const unsigned long long below = (1ull << lane) - 1ull;
@@ -432,9 +472,9 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
       __syncthreads();
     }
   }
-  // the last round of an expert pads the rest of its queue (Sec. 3: zero padding)
+  // the last round pads the rest of the capacity block (Sec. 3: zero padding)
   if (r == A.NR - 1)
-    for (int sl = fill0 + m + tid; sl < A.C; sl += SS_THREADS) slot_token[(size_t)j * A.C + sl] = -1;
+    for (int sl = fill0 + m + tid; sl < (g + 1) * A.Cq; sl += SS_THREADS) slot_token[(size_t)j * A.C + sl] = -1;
 }
 
 // ------------------------------------------------------------------ Intra-GPU lists
@@ -488,6 +528,25 @@ __global__ __launch_bounds__(64) void row_plan_kernel(DispatchArgs A, const int3
     row_base[A.E] = s_rows;
     tile_ctl[0] = min(s_tiles, A.max_mtiles);
   }
+}
+
+// Per-group quotas only: the occupied slots of an expert are not a prefix of its queue, so the
+// token behind every dispatched row is written out once (rows skip the holes between blocks).
+__global__ __launch_bounds__(256) void row_token_kernel(DispatchArgs A, const int32_t *__restrict__ slot_token,
+                                                        const int32_t *__restrict__ grp_fill,
+                                                        const int32_t *__restrict__ grp_off,
+                                                        const int32_t *__restrict__ fill_total,
+                                                        const int32_t *__restrict__ ir_offset,
+                                                        const int32_t *__restrict__ ir_token,
+                                                        const int32_t *__restrict__ row_base,
+                                                        int32_t *__restrict__ row_token) {
+  const int e = blockIdx.x, base = row_base[e];
+  for (int s = threadIdx.x; s < A.C; s += 256) {
+    const int g = s / A.Cq, p = s - g * A.Cq;
+    if (p < grp_fill[e * A.Gq + g]) row_token[base + grp_off[e * A.Gq + g] + p] = slot_token[(size_t)e * A.C + s];
+  }
+  const int nir = ir_offset[e + 1] - ir_offset[e], first = base + fill_total[e];
+  for (int t = threadIdx.x; t < nir; t += 256) row_token[first + t] = ir_token[ir_offset[e] + t];
 }
 
 // Per token: Intra-GPU list position (Sec. 4.1) and the Eq. 2 / Eq. 3 weights.
@@ -564,7 +623,8 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
 
 hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, bool ranked,
                            hipStream_t s) {
-  DispatchArgs A{D.T, D.E, D.k, D.C, D.NR, D.NCAT, D.NB, D.Eg, D.Tg, D.ir, D.fr, D.arrival, D.BM, D.max_mtiles};
+  DispatchArgs A{D.T, D.E, D.k, D.C, D.NR, D.NCAT, D.NB, D.Eg, D.Tg, D.ir, D.fr, D.arrival, D.BM, D.max_mtiles,
+                 D.Cq, D.Gq, D.NL};
   if (!ranked) {  // otherwise the router's epilogue has already written what topk_rank writes
     prof_begin(K_TOPK, s);
     topk_rank_kernel<<<D.NB, kTokBlock, 0, s>>>(logits, A, tb.rank_expert, tb.slot, W.key, W.ir_score, W.ir_cand,
@@ -575,15 +635,16 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
   scan_blocks_kernel<<<D.NCAT, SC_THREADS, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NB);
   prof_end(K_SCAN_CAND, s);
   prof_begin(K_PLAN, s);
-  plan_rounds_kernel<<<1, 64, 0, s>>>(A, W.cat_cnt, W.cat_m, W.cat_fill0, W.cat_base, tb.fill_topk, tb.fill_total);
+  plan_rounds_kernel<<<1, PL_THREADS, 0, s>>>(A, W.cat_cnt, W.blk_cnt, W.cat_base, W.lst_n, W.lst_m, W.lst_first,
+                                              W.lst_base, W.grp_fill, W.grp_off, tb.fill_topk, tb.fill_total);
   prof_end(K_PLAN, s);
   prof_begin(K_SCATTER_CAND, s);
   scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_base, W.cand_key,
                                                        W.cand_tok);
   prof_end(K_SCATTER_CAND, s);
   prof_begin(K_SELECT_SLOT, s);
-  select_slot_kernel<<<D.NCAT, SS_THREADS, 0, s>>>(A, W.cat_cnt, W.cat_m, W.cat_fill0, W.cat_base, W.cand_key,
-                                                   W.cand_tok, tb.slot, tb.slot_token);
+  select_slot_kernel<<<D.NL, SS_THREADS, 0, s>>>(A, W.lst_n, W.lst_m, W.lst_first, W.lst_base, W.cand_key, W.cand_tok,
+                                                 tb.slot, tb.slot_token);
   prof_end(K_SELECT_SLOT, s);
   if (D.ir) {
     prof_begin(K_IR_COUNT, s);
@@ -600,6 +661,9 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
   ir_weights_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.key, W.ir_score, W.ir_cand, W.ir_blk_cnt, tb.ir_offset,
                                                tb.ir_expert, tb.ir_row, tb.ir_token, tb.combine_w);
   prof_end(K_IR_WEIGHTS, s);
+  if (D.quota && D.max_mtiles > 0)  // the forward pass addresses dispatched rows through row_token
+    row_token_kernel<<<D.E, 256, 0, s>>>(A, tb.slot_token, W.grp_fill, W.grp_off, tb.fill_total, tb.ir_offset,
+                                         tb.ir_token, W.row_base, W.row_token);
   return hipGetLastError();
 }
 

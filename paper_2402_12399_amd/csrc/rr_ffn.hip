@@ -69,6 +69,7 @@ struct GemmArgs {
   const int32_t *ctl;   // [0] number of row tiles
   // GATHER only
   const int32_t *slot_token, *ir_token;
+  const int32_t *row_token;  // token of every dispatched row (per-group quotas), or NULL: rows are slots, then the Intra-GPU list
   int C;
   long long a_bytes;    // size of the A operand in bytes (buffer range of the gather)
 };
@@ -286,6 +287,7 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
     for (int i = 0; i < NIA; ++i) {
       const int lr = f.m0 + (i * NW + w) * 8 + (lane >> 3);  // row within the expert
       const int32_t *src = lr < f.fill_e ? P.slot_token + ((size_t)f.e * P.C + lr) : P.ir_token + (f.iroff_e + lr - f.fill_e);
+      if (P.row_token) src = P.row_token + (f.rbase + lr);
       if (lr >= f.rows_e) src = P.slot_token;
       tok[i] = *src;
     }
@@ -717,8 +719,8 @@ hipError_t launch_ffn_part(const Dims &D, const void *x, const rr_tables &tb, co
                            const void *w2, const Work &W, hipStream_t s, int which) {
   const bool fuse = ffn_fuses_gather(D);
   GemmArgs up{fuse ? x : W.x_disp, w1, w3, W.h, D.d, D.F, 0, W.tiles, W.tile_ctl,
-              tb.slot_token, tb.ir_token, D.C, (long long)D.T * D.d * 2};
-  GemmArgs down{W.h, w2, nullptr, W.y, D.F, D.d, 0, W.tiles, W.tile_ctl, nullptr, nullptr, 0, 0};
+              tb.slot_token, tb.ir_token, D.quota ? W.row_token : nullptr, D.C, (long long)D.T * D.d * 2};
+  GemmArgs down{W.h, w2, nullptr, W.y, D.F, D.d, 0, W.tiles, W.tile_ctl, nullptr, nullptr, nullptr, 0, 0};
   hipError_t err = hipSuccess;
   if (D.dtype == RR_BF16) {
     const bool gated = D.act == RR_ACT_SWIGLU;

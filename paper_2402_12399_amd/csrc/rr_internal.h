@@ -19,10 +19,15 @@ typedef uint32_t u32;
 
 // Everything derived from rr_config on the host.
 struct Dims {
-  int T, d, F, E, k, G, C;
+  int T, d, F, E, k, G;
+  int C;       // slots in an expert's queue (row length of slot_token)
+  int Cq;      // slots of one capacity block: C, or with per-group quotas C / G
+  int Gq;      // capacity blocks per expert: 1, or G with per-group quotas
+  int quota;
   int Eg, Tg;
   int NR;      // routing rounds that place tokens: k (+1 with Fill-in)
-  int NCAT;    // NR * E candidate lists, list id = round * E + expert
+  int NCAT;    // NR * E candidate arrays (one per round and expert, ascending token index)
+  int NL;      // NCAT * Gq selection lists: list id = (round * E + expert) * Gq + block
   int NB;      // token blocks of kTokBlock
   int ir, fr, arrival;
   int dtype, act;
@@ -45,10 +50,15 @@ struct Work {
   float   *ir_score;     // [T]       score of the best expert of the token's own group
   int32_t *ir_cand;      // [T]       that expert
   int32_t *blk_cnt;      // [NCAT, NB] candidates per (list, token block); scanned in place
-  int32_t *cat_cnt;      // [NCAT]    candidates per list
-  int32_t *cat_m;        // [NCAT]    how many of them are kept
-  int32_t *cat_fill0;    // [NCAT]    occupied slots of the expert before this round
-  int32_t *cat_base;     // [NCAT]    start of the list in cand_*
+  int32_t *cat_cnt;      // [NCAT]    candidates per (round, expert)
+  int32_t *cat_base;     // [NCAT]    start of that candidate array in cand_*
+  int32_t *lst_n;        // [NL]      candidates of a selection list (a contiguous piece of a candidate array)
+  int32_t *lst_m;        // [NL]      how many of them are kept
+  int32_t *lst_first;    // [NL]      slot of the first kept one (block start + slots occupied by earlier rounds)
+  int32_t *lst_base;     // [NL]      start of the list in cand_*
+  int32_t *grp_fill;     // [E, Gq]   occupied slots of each capacity block after the last round
+  int32_t *grp_off;      // [E, Gq]   occupied slots of the expert's earlier blocks (its dispatched rows skip the holes)
+  int32_t *row_token;    // [Rmax]    per-group quotas only: token of every dispatched row
   u32     *cand_key;     // [NR*T]    per-list candidates in ascending token index
   int32_t *cand_tok;     // [NR*T]
   int32_t *ir_blk_cnt;   // [E, NB]   Intra-GPU tokens per (expert, token block); scanned in place

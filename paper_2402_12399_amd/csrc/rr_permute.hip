@@ -1,10 +1,12 @@
 // Dispatch gather and weighted combine: on one GPU the expert-parallel all-to-all of Sec. 3 is a
 // row permutation in device memory.
 //
-// Dispatched-row layout (built by row_plan): expert e owns rows [row_base[e], row_base[e+1]); row
-// row_base[e] + s holds the token in capacity slot s (s < fill_total[e]); row
-// row_base[e] + fill_total[e] + q holds the q-th token of the expert's Intra-GPU list.  Padding
-// slots get no row: FFN(0) = 0 contributes nothing (Sec. 3, zero padding).
+// Dispatched-row layout (built by row_plan): expert e owns rows [row_base[e], row_base[e+1]): its
+// occupied capacity slots in slot order, then its Intra-GPU list.  Padding slots get no row:
+// FFN(0) = 0 contributes nothing (Sec. 3, zero padding).  Slot s of capacity block g = s / Cq is
+// row row_base[e] + grp_off[e, g] + s % Cq, where grp_off counts the occupied slots of the expert's
+// earlier blocks (one block and grp_off = 0 unless capacity is per group); row
+// row_base[e] + fill_total[e] + q holds the q-th token of the expert's Intra-GPU list.
 #include "rr_device.h"
 
 namespace rr {
@@ -43,6 +45,19 @@ __global__ __launch_bounds__(PG_THREADS) void gather_kernel(const uint4 *__restr
   for (int v = lane; v < vec_per_row; v += kWave) out[v] = src[v];
 }
 
+// Per-group quotas: x_disp[row] = x[row_token[row]] for the rows that exist (row_base[E] of them).
+__global__ __launch_bounds__(PG_THREADS) void gather_rows_kernel(const uint4 *__restrict__ x, uint4 *__restrict__ x_disp,
+                                                                 int vec_per_row, int E,
+                                                                 const int32_t *__restrict__ row_token,
+                                                                 const int32_t *__restrict__ row_base) {
+  const int q = blockIdx.x * PG_ROWS + (threadIdx.x >> 6);
+  if (q >= row_base[E]) return;
+  const int lane = lane_id();
+  const uint4 *src = x + (size_t)row_token[q] * vec_per_row;
+  uint4 *out = x_disp + (size_t)q * vec_per_row;
+  for (int v = lane; v < vec_per_row; v += kWave) out[v] = src[v];
+}
+
 __device__ inline void fma_row(float (&acc)[8], float w, const uint4 v, bool bf16) {
   if (bf16) {
     u32 p[4] = {v.x, v.y, v.z, v.w};
@@ -77,6 +92,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4 *__restrict__ 
                                                       const int32_t *__restrict__ ir_row,
                                                       const int32_t *__restrict__ fill_total,
                                                       const int32_t *__restrict__ row_base,
+                                                      const int32_t *__restrict__ grp_off, int Cq, int Gq,
                                                       const float *__restrict__ combine_w) {
   const int i = blockIdx.x;
   __shared__ int s_row[kMaxRank + 1];
@@ -87,7 +103,8 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4 *__restrict__ 
     if (r < NR) {
       int s = slot[(size_t)i * (k + 1) + r];
       if (s >= 0) {
-        row = row_base[rank_expert[(size_t)i * (k + 1) + r]] + s;
+        const int e = rank_expert[(size_t)i * (k + 1) + r], g = s / Cq;
+        row = row_base[e] + grp_off[e * Gq + g] + (s - g * Cq);
         w = combine_w[(size_t)i * (k + 2) + r];
       }
     } else if (r == kMaxRank) {
@@ -132,9 +149,13 @@ hipError_t launch_gather(const Dims &D, const void *x, const rr_tables &tb, cons
   const long long cand = (long long)D.E * D.C + (D.ir ? D.T : 0);
   const int grid = (int)((cand + PG_ROWS - 1) / PG_ROWS);
   prof_begin(K_GATHER, s);
-  gather_kernel<<<grid, PG_THREADS, 0, s>>>(static_cast<const uint4 *>(x), static_cast<uint4 *>(W.x_disp), vec_per_row,
-                                            D.E, D.C, tb.slot_token, tb.fill_total, tb.ir_offset, tb.ir_token,
-                                            tb.ir_expert, W.row_base);
+  if (D.quota)
+    gather_rows_kernel<<<(D.Rmax + PG_ROWS - 1) / PG_ROWS, PG_THREADS, 0, s>>>(
+        static_cast<const uint4 *>(x), static_cast<uint4 *>(W.x_disp), vec_per_row, D.E, W.row_token, W.row_base);
+  else
+    gather_kernel<<<grid, PG_THREADS, 0, s>>>(static_cast<const uint4 *>(x), static_cast<uint4 *>(W.x_disp), vec_per_row,
+                                              D.E, D.C, tb.slot_token, tb.fill_total, tb.ir_offset, tb.ir_token,
+                                              tb.ir_expert, W.row_base);
   prof_end(K_GATHER, s);
   return hipGetLastError();
 }
@@ -146,11 +167,11 @@ hipError_t launch_combine(const Dims &D, const rr_tables &tb, const Work &W, voi
   if (D.dtype == RR_BF16)
     combine_kernel<true><<<D.T, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out), vec_per_row,
                                              D.k, D.NR, tb.rank_expert, tb.slot, tb.ir_expert, tb.ir_row,
-                                             tb.fill_total, W.row_base, tb.combine_w);
+                                             tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w);
   else
     combine_kernel<false><<<D.T, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out), vec_per_row,
                                               D.k, D.NR, tb.rank_expert, tb.slot, tb.ir_expert, tb.ir_row,
-                                              tb.fill_total, W.row_base, tb.combine_w);
+                                              tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w);
   prof_end(K_COMBINE, s);
   return hipGetLastError();
 }

@@ -9,7 +9,7 @@ INT_TABLES = ("rank_expert", "slot", "slot_token", "fill_topk", "fill_total",
               "ir_expert", "ir_row", "ir_offset", "ir_token")
 
 
-def flags_of(mode, arrival=False):
+def flags_of(mode, arrival=False, quota=False):
     f = 0
     if "ir" in mode:
         f |= rr.RR_INTRA_GPU
@@ -17,13 +17,15 @@ def flags_of(mode, arrival=False):
         f |= rr.RR_FILL_IN
     if arrival:
         f |= rr.RR_POLICY_ARRIVAL
+    if quota:
+        f |= rr.RR_QUOTA_PER_GROUP
     return f
 
 
-def config_of(w: wl.Workload, mode=("ir", "fr"), arrival=False, T=None) -> rr.RRConfig:
+def config_of(w: wl.Workload, mode=("ir", "fr"), arrival=False, T=None, quota=False) -> rr.RRConfig:
     return rr.RRConfig(T or w.T, w.d_model, w.d_ff, w.E, w.k, w.G, w.capacity_factor,
                        rr.RR_F32 if w.dtype == "f32" else rr.RR_BF16,
-                       rr.RR_ACT_GELU if w.act == "gelu" else rr.RR_ACT_SWIGLU, flags_of(mode, arrival))
+                       rr.RR_ACT_GELU if w.act == "gelu" else rr.RR_ACT_SWIGLU, flags_of(mode, arrival, quota))
 
 
 def to_device(a, dtype):

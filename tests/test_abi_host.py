@@ -27,7 +27,7 @@ def test_every_declared_function_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "rr.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(rr_[a-z_]+)\s*\(", header))
-    assert {"rr_capacity", "rr_workspace_bytes", "rr_router_scores", "rr_rectified_dispatch", "rr_moe_forward",
+    assert {"rr_capacity", "rr_slots_per_expert", "rr_workspace_bytes", "rr_router_scores", "rr_rectified_dispatch", "rr_moe_forward",
             "rr_profile_enable", "rr_profile_read", "rr_strerror"} <= declared
     for name in declared:
         assert hasattr(lib, name), f"{name} declared in rr.h but not exported by librr.so"
@@ -47,6 +47,23 @@ def test_capacity_matches_oracle_definition():
         assert rr.rr_capacity(T, E, cf) == orc.capacity(T, E, cf), (T, E, cf)
     assert rr.rr_capacity(0, 8, 1.0) == -1 and rr.rr_capacity(8, 0, 1.0) == -1
     assert rr.rr_capacity(8, 8, 0.0) == -1 and rr.rr_capacity(8, 8, float("nan")) == -1
+
+
+def test_slots_per_expert_matches_oracle_definition():
+    rng = np.random.default_rng(1)
+    for _ in range(300):
+        G = int(rng.choice([1, 2, 4, 8]))
+        E = G * int(rng.integers(1, 64 // G + 1))
+        T = G * 128 * int(rng.integers(1, 200))
+        cf = float(np.float32(rng.choice([0.25, 0.5, 0.75, 1.0, 1.25, 2.0, 0.001])))
+        k = 1 if E < 3 else 2
+        base = dict(T=T, E=E, G=G, k=k, capacity_factor=cf)
+        flags = rr.RR_INTRA_GPU | (rr.RR_FILL_IN if E > k else 0)
+        assert rr.rr_slots_per_expert(_cfg(flags=flags, **base)) == orc.capacity(T, E, cf)
+        assert rr.rr_slots_per_expert(_cfg(flags=flags | rr.RR_QUOTA_PER_GROUP, **base)) == G * orc.capacity(T // G, E, cf)
+    with pytest.raises(rr.RRError):
+        rr.rr_slots_per_expert(_cfg(flags=rr.RR_QUOTA_PER_GROUP, T=1000))
+    assert rr.load_library().rr_slots_per_expert(None) == -1
 
 
 def test_strerror(lib):
@@ -80,6 +97,10 @@ def _ws_status(lib, cfg):
     (dict(E=128, G=2), UNSUPPORTED), (dict(k=5, E=8), UNSUPPORTED), (dict(dtype=7), UNSUPPORTED),
     (dict(d_model=60), UNSUPPORTED), (dict(d_ff=100), UNSUPPORTED), (dict(act=5), UNSUPPORTED),
     (dict(T=1 << 25, G=2), UNSUPPORTED),
+    (dict(flags=rr.RR_QUOTA_PER_GROUP | rr.RR_INTRA_GPU | rr.RR_FILL_IN), RR_OK),   # 512 tokens per group
+    (dict(flags=rr.RR_QUOTA_PER_GROUP, T=1000), UNSUPPORTED),                      # groups must hold whole token blocks
+    (dict(flags=rr.RR_QUOTA_PER_GROUP, T=1024, G=8, E=8), RR_OK),
+    (dict(flags=rr.RR_QUOTA_PER_GROUP, T=1024 + 8, G=8, E=8), UNSUPPORTED),
 ])
 def test_config_validation(lib, kw, want):
     assert _ws_status(lib, _cfg(**kw))[0] == want

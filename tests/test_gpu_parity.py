@@ -18,9 +18,9 @@ pytestmark = pytest.mark.gpu
 MODES = [(), ("ir",), ("fr",), ("ir", "fr")]
 
 
-def _oracle_tables(a, cfg, mode, arrival=False):
+def _oracle_tables(a, cfg, mode, arrival=False, quota=False):
     return orc.route(a, cfg.k, cfg.G, cfg.capacity_factor, "ir" in mode, "fr" in mode,
-                     orc.POLICY_ARRIVAL if arrival else orc.POLICY_SCORE)
+                     orc.POLICY_ARRIVAL if arrival else orc.POLICY_SCORE, quota)
 
 
 # ------------------------------------------------------------------ routing tables, identical logits
@@ -109,8 +109,8 @@ def test_router_scores(dtype, T, d, E, k):
 
 
 # ------------------------------------------------------------------ whole layer
-def _forward_case(w, mode, inputs, tol, sample=None, arrival=False):
-    cfg = gu.config_of(w, mode, arrival, T=inputs["x"].shape[0])
+def _forward_case(w, mode, inputs, tol, sample=None, arrival=False, quota=False):
+    cfg = gu.config_of(w, mode, arrival, T=inputs["x"].shape[0], quota=quota)
     dev = {n: (torch.from_numpy(inputs[n]).cuda() if n in ("w_router", "bias") and inputs[n] is not None
                else gu.to_device(inputs[n], w.dtype)) for n in ("x", "w_router", "bias", "w1", "w3", "w2")}
     out, tables, logits = gu.run_forward(cfg, dev)
@@ -118,7 +118,7 @@ def _forward_case(w, mode, inputs, tol, sample=None, arrival=False):
     a, want_tables, want_out = orc.moe_forward(
         f32("x"), inputs["w_router"], inputs["bias"], f32("w1"), f32("w3"), f32("w2"), w.k, w.G,
         w.capacity_factor, w.act, "ir" in mode, "fr" in mode,
-        orc.POLICY_ARRIVAL if arrival else orc.POLICY_SCORE, tokens=sample)
+        orc.POLICY_ARRIVAL if arrival else orc.POLICY_SCORE, tokens=sample, quota=quota)
     assert gu.rel_l2(logits.astype(np.float64), a.astype(np.float64)) <= 1e-5
     gu.assert_tables_equal(tables, want_tables, cw_atol=2e-5)  # weights from logits that differ by rounding
     got = gu.to_host_f64(out)
@@ -161,16 +161,16 @@ def test_forward_small(w, mode):
     _forward_case(w, mode, wl.make_inputs(w), 1e-5 if w.dtype == "f32" else 2e-2)
 
 
-def _full_size_case(w, mode, n_sample=1024):
+def _full_size_case(w, mode, n_sample=1024, quota=False):
     """Full-size workload in the configuration the benchmark times; oracle outputs on a token sample."""
     dev = wl.make_inputs_device(w)
-    cfg = gu.config_of(w, mode)
+    cfg = gu.config_of(w, mode, quota=quota)
     out, tables, logits = gu.run_forward(cfg, dev)
     x = wl.values_f32(gu.to_host_storage(dev["x"]), w.dtype)
     wr, b = dev["w_router"].cpu().numpy(), None if dev["bias"] is None else dev["bias"].cpu().numpy()
     a = orc.router_scores(x, wr, b)
     assert gu.rel_l2(logits.astype(np.float64), a.astype(np.float64)) <= 1e-5
-    want = orc.route(a, w.k, w.G, w.capacity_factor, "ir" in mode, "fr" in mode)
+    want = orc.route(a, w.k, w.G, w.capacity_factor, "ir" in mode, "fr" in mode, quota=quota)
     gu.assert_tables_equal(tables, want, cw_atol=2e-5)
     sample = np.sort(np.random.default_rng(w.seed).choice(w.T, n_sample, replace=False))
 
@@ -269,3 +269,91 @@ def test_routing_only_forward_large_batch(dtype, E, k, G):
     assert np.array_equal(logits.cpu().numpy(), a)
     assert np.array_equal(ranks.cpu().numpy(), orc.rank_experts(a, k + 1))
     assert np.abs(probs.cpu().numpy() - orc.softmax_probs(a)).max() <= 1e-6
+
+
+# ------------------------------------------------------------------ capacity per group (Sec. 3 capacity read per GPU)
+QUOTA_CASES = [
+    # T, E, G, k, cf, ties
+    (256, 8, 2, 1, 1.0, False),        # one token block per group
+    (1024, 8, 1, 2, 1.25, False),      # one group: the global reading
+    (1536, 6, 3, 2, 0.5, True),        # E and G not powers of two, many ties
+    (8 * 128, 64, 8, 2, 0.75, False),  # per-group capacity of 2 slots
+    (8 * 640, 64, 8, 4, 2.0, True),    # largest k
+    (2 * 384, 4, 2, 3, 3.0, False),    # k+1 == E
+    (2 * 128, 2, 2, 2, 1.0, True),     # k == E
+    (5 * 4096, 30, 5, 1, 0.5, False),
+    (2 * 33792, 16, 2, 2, 1.0, True),
+]
+
+
+@pytest.mark.parametrize("T,E,G,k,cf,ties", QUOTA_CASES)
+@pytest.mark.parametrize("mode", MODES, ids=["vanilla", "ir", "fr", "ir+fr"])
+def test_quota_dispatch_tables_bit_exact(T, E, G, k, cf, ties, mode):
+    if "fr" in mode and k + 1 > E:
+        pytest.skip("Fill-in needs k+1 <= E")
+    a = wl.synthetic_logits(T, E, seed=T + E + k + 1, bias_std=1.0, ties=ties)
+    for arrival in (False, True):
+        cfg = rr.RRConfig(T, 64, 0, E, k, G, cf, rr.RR_F32, rr.RR_ACT_SWIGLU, gu.flags_of(mode, arrival, quota=True))
+        assert rr.rr_slots_per_expert(cfg) == G * orc.capacity(T // G, E, cf)
+        got = gu.run_dispatch(cfg, a)
+        gu.assert_tables_equal(got, _oracle_tables(a, cfg, mode, arrival, quota=True))
+
+
+def test_quota_dispatch_extreme_cases():
+    # every token wants the same expert; per-group capacity 1; per-group capacity >= T/G; all scores equal
+    T, E, G = 1024, 8, 4
+    a = np.zeros((T, E), dtype=np.float32)
+    a[:, 3] = 5.0
+    flags = gu.flags_of(("ir", "fr"), quota=True)
+    for cf, k in [(1.0, 1), (0.001, 2), (float(E), 2)]:
+        cfg = rr.RRConfig(T, 64, 0, E, k, G, cf, rr.RR_F32, rr.RR_ACT_SWIGLU, flags)
+        gu.assert_tables_equal(gu.run_dispatch(cfg, a), _oracle_tables(a, cfg, ("ir", "fr"), quota=True))
+    a[:] = 1.0
+    cfg = rr.RRConfig(T, 64, 0, E, 2, G, 1.0, rr.RR_F32, rr.RR_ACT_SWIGLU, flags)
+    gu.assert_tables_equal(gu.run_dispatch(cfg, a), _oracle_tables(a, cfg, ("ir", "fr"), quota=True))
+    # candidate lists of one group longer than the selection keeps in registers
+    Tb = 2 * 32768
+    a = wl.synthetic_logits(Tb, 4, seed=22, ties=True)
+    a[:, 1] += 6.0
+    cfg = rr.RRConfig(Tb, 64, 0, 4, 2, 2, 1.0, rr.RR_F32, rr.RR_ACT_SWIGLU, flags)
+    gu.assert_tables_equal(gu.run_dispatch(cfg, a), _oracle_tables(a, cfg, ("ir", "fr"), quota=True))
+    a = wl.synthetic_logits(T, E, seed=21)
+    # one group is starved of an expert that the other floods: the flooded group may not borrow the idle slots
+    a[: T // 2, 0] += 8.0
+    a[T // 2:, 0] -= 8.0
+    cfg = rr.RRConfig(T, 64, 0, E, 1, 2, 1.0, rr.RR_F32, rr.RR_ACT_SWIGLU, flags)
+    got = gu.run_dispatch(cfg, a)
+    gu.assert_tables_equal(got, _oracle_tables(a, cfg, ("ir", "fr"), quota=True))
+    Cq = orc.capacity(T // 2, E, 1.0)
+    assert (got["slot_token"][0, :Cq] >= 0).all() and (got["slot_token"][0, :Cq] < T // 2).all()
+    assert ((got["slot_token"][0, Cq:] >= T // 2) | (got["slot_token"][0, Cq:] < 0)).all()
+
+
+def test_quota_c4_routing_full_size():
+    w = wl.C4
+    cfg = gu.config_of(w, quota=True)
+    a = wl.synthetic_logits(w.T, w.E, seed=5, bias_std=0.3)
+    gu.assert_tables_equal(gu.run_dispatch(cfg, a), orc.route(a, w.k, w.G, w.capacity_factor, True, True, quota=True))
+
+
+@pytest.mark.parametrize("mode", MODES, ids=["vanilla", "ir", "fr", "ir+fr"])
+def test_quota_forward_c1_fp32(mode):
+    _forward_case(wl.C1, mode, wl.make_inputs(wl.C1), 1e-5, quota=True)
+
+
+QUOTA_SMALL = [w for w in SMALL_BF16 if (w.T // w.G) * w.G == w.T and (w.T // w.G) % 128 == 0]
+
+
+@pytest.mark.parametrize("w", QUOTA_SMALL, ids=[w.name for w in QUOTA_SMALL])
+@pytest.mark.parametrize("mode", [(), ("ir", "fr")], ids=["vanilla", "ir+fr"])
+def test_quota_forward_small(w, mode):
+    _forward_case(w, mode, wl.make_inputs(w), 1e-5 if w.dtype == "f32" else 2e-2, quota=True)
+
+
+@pytest.mark.parametrize("mode", [(), ("ir", "fr")], ids=["vanilla", "ir+fr"])
+def test_quota_forward_c2_full_size(mode):
+    _full_size_case(wl.C2, mode, quota=True)
+
+
+def test_quota_forward_c5_full_size():
+    _full_size_case(wl.C5, ("ir", "fr"), n_sample=512, quota=True)
