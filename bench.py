@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--mode", default="ir+fr", help="vanilla | ir | fr | ir+fr")
+    ap.add_argument("--quota", action="store_true",
+                    help="capacity per group (RR_QUOTA_PER_GROUP) instead of one queue per expert over all tokens")
     ap.add_argument("--cpu-sample", type=int, default=2048, help="tokens the CPU oracle computes outputs for (0 = skip)")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the headline workload: skip the paper-shape (c3) and routing-stress (c4) extras")
@@ -83,9 +85,10 @@ def hbm_rooflines(kernels, hbm):
     return out
 
 
-def run_forward(rr, wl, torch, w, mode, steps, warmup):
+def run_forward(rr, wl, torch, w, mode, steps, warmup, quota=False):
     """Times rr_moe_forward on one workload; returns the numbers the JSON line is built from."""
     flags = (rr.RR_INTRA_GPU if "ir" in mode else 0) | (rr.RR_FILL_IN if "fr" in mode else 0)
+    flags |= rr.RR_QUOTA_PER_GROUP if quota else 0
     cfg = rr.RRConfig(w.T, w.d_model, w.d_ff, w.E, w.k, w.G, w.capacity_factor,
                       rr.RR_F32 if w.dtype == "f32" else rr.RR_BF16,
                       rr.RR_ACT_GELU if w.act == "gelu" else rr.RR_ACT_SWIGLU, flags)
@@ -215,11 +218,14 @@ def cf_sweep(rr, wl, torch, steps, warmup):
     points = [(1, cf, 2, m) for cf in (0.5, 0.75, 1.0, 1.25, 1.5) for m in modes]
     points += [(2, cf, 2, m) for cf in (1.0, 1.5, 2.0, 2.5, 3.0) for m in modes]
     points += [(k, cf, G, "ir") for (k, cf) in ((1, 1.0), (2, 2.0)) for G in (8, 4)]  # 1 and 2 experts per GPU
+    # the same layer with capacity read per GPU (each group fills its own block of every expert's queue)
+    points += [(k, cf, G, m + "/per-group") for (k, cf) in ((1, 1.0), (2, 1.25)) for G in (2, 8) for m in ("vanilla", "ir+fr")]
     rows = []
     for k, cf, G, m in points:
         w = dataclasses.replace(base, k=k, capacity_factor=cf, G=G)
+        per_group = m.endswith("/per-group")
         cfg = rr.RRConfig(w.T, w.d_model, w.d_ff, w.E, w.k, w.G, w.capacity_factor, rr.RR_BF16, rr.RR_ACT_SWIGLU,
-                          modes[m])
+                          modes[m.split("/")[0]] | (rr.RR_QUOTA_PER_GROUP if per_group else 0))
         tables = rr.alloc_tables(cfg)
         ws = rr.alloc_workspace(cfg)
 
@@ -278,12 +284,12 @@ def main():
         return 0
     mode = () if args.mode == "vanilla" else tuple(args.mode.split("+"))
     torch.cuda.set_device(0)
-    res = run_forward(rr, wl, torch, w, mode, args.steps, args.warmup)
+    res = run_forward(rr, wl, torch, w, mode, args.steps, args.warmup, args.quota)
     dev = res.pop("dev")
 
     cpu = None
     if args.cpu_sample > 0:
-        cpu = cpu_baseline(w, mode, dev, min(args.cpu_sample, w.T))
+        cpu = cpu_baseline(w, mode, dev, min(args.cpu_sample, w.T), args.quota)
     del dev
     torch.cuda.empty_cache()
 
@@ -312,7 +318,8 @@ def main():
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": w.name, "mode": "top%d" % w.k + "".join("+" + m for m in mode), "T": w.T,
                    "d_model": w.d_model, "d_ff": w.d_ff, "E": w.E, "k": w.k, "G": w.G,
-                   "capacity_factor": w.capacity_factor, "capacity": res["capacity"], "act": w.act, "router": "fp32",
+                   "capacity_factor": w.capacity_factor, "capacity": res["capacity"],
+                   "capacity_scope": "per group" if args.quota else "all tokens", "act": w.act, "router": "fp32",
                    "parallelism": "1 GPU, %d simulated expert-parallel groups" % w.G},
         "roofline": res["roofline"],
         "cpu_baseline": cpu,
@@ -378,7 +385,7 @@ def routing_stress(rr, wl, torch, steps, warmup):
                                 "frac": gbs / PEAK_HBM_GBS, "bytes_per_launch": router_bytes}}
 
 
-def cpu_baseline(w, mode, dev, n_sample):
+def cpu_baseline(w, mode, dev, n_sample, quota=False):
     """The CPU oracle as it stands, timed on this host: routing of the full batch plus expert
     outputs for the first n_sample tokens, scaled to tokens/s of the whole layer."""
     from oracle import rectify_router as orc
@@ -400,7 +407,7 @@ def cpu_baseline(w, mode, dev, n_sample):
         cores = int(os.environ.get("OMP_NUM_THREADS", "1"))
     t0 = time.perf_counter()
     a = orc.router_scores(h["x"], h["w_router"], h["bias"])
-    tb = orc.route(a, w.k, w.G, w.capacity_factor, "ir" in mode, "fr" in mode)
+    tb = orc.route(a, w.k, w.G, w.capacity_factor, "ir" in mode, "fr" in mode, quota=quota)
     t_route = time.perf_counter() - t0
     sample = np.arange(n_sample)
     t0 = time.perf_counter()
