@@ -156,8 +156,8 @@ def run_forward(rr, wl, torch, w, mode, steps, warmup, quota=False):
     if dom in flops:
         roofline["flops_per_launch"] = flops[dom]
     ffn_ms = kernels.get("ffn_gate_up", 0) + kernels.get("ffn_down", 0)
-    routing_names = ("router_scores", "topk_rank", "scan_candidates", "plan_rounds", "scatter_candidates",
-                     "select_slot", "ir_count", "ir_scan", "row_plan", "ir_weights")
+    routing_names = ("router_scores", "topk_rank", "scan_candidates", "scatter_candidates",
+                     "select_slot", "ir_count", "ir_scan", "ir_weights")
     routing_ms = sum(kernels.get(n, 0.0) for n in routing_names)
     return {
         "dev": dev, "capacity": C, "ms_per_step": ms_per_step, "tokens_per_s": T / (ms_per_step * 1e-3),

@@ -15,8 +15,8 @@ static std::vector<ProfSpan> g_spans;       // recorded launches since the last 
 static std::vector<hipEvent_t> g_free_events;
 static hipEvent_t g_open[K_COUNT];
 static const char *const g_kernel_names[K_COUNT] = {
-    "router_scores", "topk_rank", "scan_candidates", "plan_rounds", "scatter_candidates", "select_slot",
-    "ir_count", "ir_scan", "row_plan", "ir_weights", "dispatch_gather", "ffn_gate_up", "ffn_down", "combine"};
+    "router_scores", "topk_rank", "scan_candidates", "scatter_candidates", "select_slot",
+    "ir_count", "ir_scan", "ir_weights", "dispatch_gather", "ffn_gate_up", "ffn_down", "combine"};
 
 static hipEvent_t get_event() {
   if (!g_free_events.empty()) {
@@ -111,11 +111,6 @@ static size_t carve(const Dims &D, bool forward, void *ws, Work *W) {
   W->ir_cand = cv.take<int32_t>(T);
   W->blk_cnt = cv.take<int32_t>((size_t)D.NCAT * D.NB);
   W->cat_cnt = cv.take<int32_t>(D.NCAT);
-  W->cat_base = cv.take<int32_t>(D.NCAT);
-  W->lst_n = cv.take<int32_t>(D.NL);
-  W->lst_m = cv.take<int32_t>(D.NL);
-  W->lst_first = cv.take<int32_t>(D.NL);
-  W->lst_base = cv.take<int32_t>(D.NL);
   W->grp_fill = cv.take<int32_t>(E * D.Gq);
   W->grp_off = cv.take<int32_t>(E * D.Gq);
   W->row_token = D.quota ? cv.take<int32_t>(D.Rmax) : nullptr;

@@ -9,13 +9,16 @@
 //   topk_rank          per token: ranked experts, score keys, best expert of its own group,
 //                      candidate counts per (list, token block)
 //   scan_candidates    exclusive scan of those counts over token blocks, per list
-//   plan_rounds        per expert: kept counts and first free slot of every round
 //   scatter_candidates stable split of the tokens into per-list arrays (ascending token index)
-//   select_slot        per list: radix-select the score threshold of the kept set (ties -> lower
-//                      token index), then a prefix scan in token order hands out consecutive slots
-//   ir_count / ir_scan / row_plan / ir_weights
+//   select_slot        per list: kept count and first free slot from the counts, radix-select of
+//                      the score threshold of the kept set (ties -> lower token index), then a
+//                      prefix scan in token order hands out consecutive slots
+//   ir_count / ir_scan / ir_weights
 //                      per-expert Intra-GPU lists (stable, token order), dispatched-row layout and
 //                      row tiles for the grouped GEMM, combine weights
+// Plans that are a few dozen numbers (array bases, kept counts, row layout) are recomputed by every
+// workgroup that needs them instead of being a launch of their own: a dependent launch costs about
+// 6 us on this part, more than any of these kernels needs for a small batch.
 // Every table is a deterministic function of the logits: integer atomics are only used for counts.
 #include "rr_device.h"
 
@@ -171,90 +174,33 @@ __global__ __launch_bounds__(SC_THREADS) void scan_blocks_kernel(int32_t *__rest
   if (tid == 0) tot[blockIdx.x] = running;
 }
 
-// ------------------------------------------------------------------ plan_rounds
-// A selection list is the piece of a (round, expert) candidate array that competes for one capacity
-// block: the whole array and the expert's whole queue by default; with per-group quotas (Sec. 3's
-// capacity read per GPU) the candidates of group g - a contiguous piece, since candidates are in
-// ascending token index and groups are token ranges that end on block boundaries - and the group's
-// Cq slots.  Per list: candidates, kept count min(candidates, free slots of the block), first slot.
-constexpr int PL_THREADS = 1024;
-__global__ __launch_bounds__(PL_THREADS) void plan_rounds_kernel(DispatchArgs A, const int32_t *__restrict__ cat_cnt,
-                                                                 const int32_t *__restrict__ blk_off,
-                                                                 int32_t *__restrict__ cat_base,
-                                                                 int32_t *__restrict__ lst_n, int32_t *__restrict__ lst_m,
-                                                                 int32_t *__restrict__ lst_first,
-                                                                 int32_t *__restrict__ lst_base,
-                                                                 int32_t *__restrict__ grp_fill,
-                                                                 int32_t *__restrict__ grp_off,
-                                                                 int32_t *__restrict__ fill_topk,
-                                                                 int32_t *__restrict__ fill_total) {
-  __shared__ int s_base[kMaxRounds * kMaxE];
-  __shared__ int s_topk[kMaxE * kMaxE];  // occupied slots per (expert, block) after the top-k rounds
-  const int tid = threadIdx.x;
-  // every token is a candidate of exactly one array per round: round r's arrays tile [r T, (r+1) T)
-  if (tid < kWave) {
-    for (int r = 0; r < A.NR; ++r) {
-      const int c = tid < A.E ? cat_cnt[r * A.E + tid] : 0;
-      int incl = c;
-#pragma unroll
-      for (int off = 1; off < 64; off <<= 1) {
-        int t = __shfl_up(incl, off);
-        if (tid >= off) incl += t;
-      }
-      if (tid < A.E) {
-        s_base[r * A.E + tid] = r * A.T + incl - c;
-        cat_base[r * A.E + tid] = r * A.T + incl - c;
-      }
-    }
-  }
-  __syncthreads();
-  const int bpg = A.NB / A.Gq;  // token blocks per group (exact with quotas; all of them otherwise)
-  for (int p = tid; p < A.E * A.Gq; p += PL_THREADS) {
-    const int j = p / A.Gq, g = p - j * A.Gq;
-    int fill = 0;
-    for (int r = 0; r < A.NR; ++r) {
-      const int cat = r * A.E + j;
-      const int lo = g == 0 ? 0 : blk_off[(size_t)cat * A.NB + g * bpg];
-      const int hi = g == A.Gq - 1 ? cat_cnt[cat] : blk_off[(size_t)cat * A.NB + (g + 1) * bpg];
-      const int q = cat * A.Gq + g;
-      const int m = min(hi - lo, A.Cq - fill);
-      lst_n[q] = hi - lo;
-      lst_m[q] = m;
-      lst_first[q] = g * A.Cq + fill;
-      lst_base[q] = s_base[cat] + lo;
-      fill += m;
-      if (r == A.k - 1) s_topk[p] = fill;
-    }
-    grp_fill[p] = fill;
-  }
-  __syncthreads();
-  __threadfence_block();
-  if (tid < A.E) {
-    int topk = 0, total = 0;
-    for (int g = 0; g < A.Gq; ++g) {
-      grp_off[tid * A.Gq + g] = total;
-      topk += s_topk[tid * A.Gq + g];
-      total += grp_fill[tid * A.Gq + g];
-    }
-    fill_topk[tid] = topk;
-    fill_total[tid] = total;
-  }
-}
-
 // ------------------------------------------------------------------ scatter_candidates
 __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchArgs A,
                                                                        const int32_t *__restrict__ rank_expert,
                                                                        const u32 *__restrict__ key,
                                                                        const int32_t *__restrict__ blk_off,
-                                                                       const int32_t *__restrict__ cat_base,
+                                                                       const int32_t *__restrict__ cat_cnt,
                                                                        u32 *__restrict__ cand_key,
                                                                        int32_t *__restrict__ cand_tok) {
   constexpr int NW = kTokBlock / kWave;
   __shared__ int wcnt[kMaxRounds][NW][kMaxE];
-  const int tid = threadIdx.x, b = xcd_block(blockIdx.x, A.NB), w = tid >> 6;
+  __shared__ int s_base[kMaxRounds * kMaxE];
+  const int tid = threadIdx.x, b = xcd_block(blockIdx.x, A.NB), w = tid >> 6, lane = tid & 63;
   const int i = b * kTokBlock + tid;
   const bool valid = i < A.T;
   for (int c = tid; c < kMaxRounds * NW * kMaxE; c += kTokBlock) (&wcnt[0][0][0])[c] = 0;
+  // every token is a candidate of exactly one array per round: round r's arrays tile [r T, (r+1) T)
+  // in expert order (a dozen counts: recomputed by every workgroup rather than by a launch of its own)
+  for (int r = w; r < A.NR; r += NW) {
+    const int c = lane < A.E ? cat_cnt[r * A.E + lane] : 0;
+    int incl = c;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      int t = __shfl_up(incl, off);
+      if (lane >= off) incl += t;
+    }
+    if (lane < A.E) s_base[r * A.E + lane] = r * A.T + incl - c;
+  }
   __syncthreads();
   int e_r[kMaxRounds], rank_r[kMaxRounds];
 #pragma unroll
@@ -276,7 +222,7 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
   for (int r = 0; r < kMaxRounds; ++r) {
     if (r < A.NR) {
       int e = e_r[r], cat = r * A.E + e;
-      int pos = cat_base[cat] + blk_off[(size_t)cat * A.NB + b] + rank_r[r];
+      int pos = s_base[cat] + blk_off[(size_t)cat * A.NB + b] + rank_r[r];
       for (int q = 0; q < w; ++q) pos += wcnt[r][q][e];
       cand_key[pos] = key[(size_t)i * A.NR + r];
       cand_tok[pos] = i;
@@ -334,24 +280,77 @@ __device__ inline u32 radix_select(int m, Each each, u32 *hist, u32 *s_pick, u32
   return prefix;
 }
 
-__global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A, const int32_t *__restrict__ lst_n,
-                                                                 const int32_t *__restrict__ lst_m,
-                                                                 const int32_t *__restrict__ lst_first,
-                                                                 const int32_t *__restrict__ lst_base,
+// A selection list is the piece of a (round, expert) candidate array that competes for one capacity
+// block: the whole array and the expert's whole queue by default; with per-group quotas (Sec. 3's
+// capacity read per GPU) the candidates of group g - a contiguous piece, since candidates are in
+// ascending token index and groups are token ranges that end on block boundaries - and the group's
+// Cq slots.  The kept count of a round is min(candidates, free slots of the block), so every round
+// (Fill-in, the (k+1)-th, included) is planned from the candidate counts alone; each workgroup derives
+// its own list's numbers from them, and the workgroup of an expert's last round and first block also
+// writes the expert's fill counts.
+__global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A, const int32_t *__restrict__ cat_cnt,
+                                                                 const int32_t *__restrict__ blk_off,
                                                                  const u32 *__restrict__ cand_key,
                                                                  const int32_t *__restrict__ cand_tok,
                                                                  int32_t *__restrict__ slot,
-                                                                 int32_t *__restrict__ slot_token) {
+                                                                 int32_t *__restrict__ slot_token,
+                                                                 int32_t *__restrict__ grp_fill,
+                                                                 int32_t *__restrict__ grp_off,
+                                                                 int32_t *__restrict__ fill_topk,
+                                                                 int32_t *__restrict__ fill_total) {
   __shared__ u32 hist[256];
   __shared__ u32 s_pick[2];
   __shared__ int2 wtot[SS_PER][SS_WAVES];  // (kept-for-sure, equal-to-threshold) counts per (trip, wave)
   __shared__ int2 wsum[8];
-  // list = (round r, expert j, capacity block g); fill0 = first slot of this round's kept tokens
+  // list = (round r, expert j, capacity block g); n candidates, m of them kept, in slots fill0 ..
   const int lst = blockIdx.x, cat = lst / A.Gq, g = lst - cat * A.Gq, r = cat / A.E, j = cat - r * A.E;
-  const int n = lst_n[lst], m = lst_m[lst], fill0 = lst_first[lst];
-  const u32 *keys = cand_key + lst_base[lst];
-  const int32_t *toks = cand_tok + lst_base[lst];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int bpg = A.NB / A.Gq;  // token blocks per group (exact with quotas; all of them otherwise)
+  // candidates [lo, hi) of (round rr, expert j) that belong to group gg
+  auto piece = [&](int rr, int gg, int &lo, int &hi) {
+    const int c = rr * A.E + j;
+    lo = gg == 0 ? 0 : blk_off[(size_t)c * A.NB + gg * bpg];
+    hi = gg == A.Gq - 1 ? cat_cnt[c] : blk_off[(size_t)c * A.NB + (gg + 1) * bpg];
+  };
+  int n = 0, m = 0, fill = 0, lo = 0;
+  for (int rr = 0; rr <= r; ++rr) {
+    int hi;
+    fill += m;
+    piece(rr, g, lo, hi);
+    n = hi - lo;
+    m = min(n, A.Cq - fill);
+  }
+  const int fill0 = g * A.Cq + fill;
+  int base = r * A.T + lo;  // round r's arrays tile [r T, (r+1) T) in expert order
+  for (int jj = 0; jj < j; ++jj) base += cat_cnt[r * A.E + jj];
+  const u32 *keys = cand_key + base;
+  const int32_t *toks = cand_tok + base;
+  if (r == A.NR - 1 && g == 0 && w == 0) {
+    // lane gg: occupied slots of block gg after the top-k rounds and after every round
+    int topk = 0, total = 0;
+    if (lane < A.Gq) {
+      for (int rr = 0; rr < A.NR; ++rr) {
+        int l, h;
+        piece(rr, lane, l, h);
+        total += min(h - l, A.Cq - total);
+        if (rr == A.k - 1) topk = total;
+      }
+    }
+    int incl = total, sum_topk = topk;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int t = __shfl_up(incl, off);
+      if (lane >= off) incl += t;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) sum_topk += __shfl_xor(sum_topk, off);
+    if (lane < A.Gq) {
+      grp_fill[j * A.Gq + lane] = total;
+      grp_off[j * A.Gq + lane] = incl - total;
+    }
+    if (lane == 63) fill_total[j] = incl;
+    if (lane == 0) fill_topk[j] = sum_topk;
+  }
   const bool by_score = !A.arrival || r == A.k;  // the Fill-in round always selects by score (Sec. 4.2)
   const unsigned long long below = (1ull << lane) - 1ull;
 
@@ -498,13 +497,15 @@ __global__ __launch_bounds__(kTokBlock) void ir_count_kernel(DispatchArgs A, con
 }
 
 // Dispatched-row layout: expert e owns rows [row_base[e], row_base[e+1]): its occupied capacity
-// slots first, then its Intra-GPU rows.  Also cuts every expert's rows into tiles of BM rows
-// (skipped when max_mtiles == 0: routing-only calls have no grouped GEMM).
-__global__ __launch_bounds__(64) void row_plan_kernel(DispatchArgs A, const int32_t *__restrict__ fill_total,
-                                                      const int32_t *__restrict__ ir_cnt,
-                                                      int32_t *__restrict__ ir_offset, int32_t *__restrict__ row_base,
-                                                      TileInfo *__restrict__ tiles, int32_t *__restrict__ tile_ctl) {
-  const int e = threadIdx.x;  // one lane per expert, E <= 64 = one wave
+// slots first, then its Intra-GPU rows.  One wave, lane e = expert e: the offsets of the experts'
+// Intra-GPU lists go to s_off (LDS, every workgroup of ir_weights needs them); the wave that `writes`
+// also stores them with row_base and cuts every expert's rows into tiles of BM rows (skipped when
+// max_mtiles == 0: routing-only calls have no grouped GEMM).
+__device__ inline void row_plan_wave(const DispatchArgs &A, bool writes, const int32_t *__restrict__ fill_total,
+                                     const int32_t *__restrict__ ir_cnt, int *s_off, int32_t *__restrict__ ir_offset,
+                                     int32_t *__restrict__ row_base, TileInfo *__restrict__ tiles,
+                                     int32_t *__restrict__ tile_ctl) {
+  const int e = threadIdx.x & 63;
   const bool on = e < A.E;
   const int nir = (on && A.ir) ? ir_cnt[e] : 0;
   const int fill = on ? fill_total[e] : 0;
@@ -516,6 +517,8 @@ __global__ __launch_bounds__(64) void row_plan_kernel(DispatchArgs A, const int3
     int a = __shfl_up(s_ir, off), b = __shfl_up(s_rows, off), c = __shfl_up(s_tiles, off);
     if (e >= off) { s_ir += a; s_rows += b; s_tiles += c; }
   }
+  if (on) s_off[e] = s_ir - nir;
+  if (!writes) return;
   if (on) {
     ir_offset[e] = s_ir - nir;
     row_base[e] = s_rows - rows;
@@ -555,17 +558,26 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
                                                                const float *__restrict__ ir_score,
                                                                const int32_t *__restrict__ ir_cand,
                                                                const int32_t *__restrict__ ir_blk_off,
-                                                               const int32_t *__restrict__ ir_offset,
+                                                               const int32_t *__restrict__ ir_cnt,
+                                                               const int32_t *__restrict__ fill_total,
+                                                               int32_t *__restrict__ ir_offset,
+                                                               int32_t *__restrict__ row_base,
+                                                               TileInfo *__restrict__ tiles,
+                                                               int32_t *__restrict__ tile_ctl,
                                                                int32_t *__restrict__ ir_expert,
                                                                int32_t *__restrict__ ir_row,
                                                                int32_t *__restrict__ ir_token,
                                                                float *__restrict__ combine_w) {
   constexpr int NW = kTokBlock / kWave;
   __shared__ int wcnt[NW][kMaxE];
+  __shared__ int s_off[kMaxE];
   const int tid = threadIdx.x, b = xcd_block(blockIdx.x, A.NB), w = tid >> 6;
   const int i = b * kTokBlock + tid;
   const bool valid = i < A.T;
   for (int c = tid; c < NW * kMaxE; c += kTokBlock) (&wcnt[0][0])[c] = 0;
+  // the row plan is a few dozen numbers: every workgroup recomputes the list offsets it needs, the
+  // first one also writes the plan out for the kernels that follow
+  if (w == 0) row_plan_wave(A, blockIdx.x == 0, fill_total, ir_cnt, s_off, ir_offset, row_base, tiles, tile_ctl);
   __syncthreads();
   int ndrop = 0;
   if (valid) ndrop = drops_of_token(slot, i, A.k);
@@ -582,7 +594,7 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
     for (int q = 0; q < w; ++q) row += wcnt[q][h];
     ir_expert[i] = h;
     ir_row[i] = row;
-    ir_token[ir_offset[h] + row] = i;
+    ir_token[s_off[h] + row] = i;
     a_h = ir_score[i];
   } else {
     ir_expert[i] = -1;
@@ -634,17 +646,13 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
   prof_begin(K_SCAN_CAND, s);
   scan_blocks_kernel<<<D.NCAT, SC_THREADS, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NB);
   prof_end(K_SCAN_CAND, s);
-  prof_begin(K_PLAN, s);
-  plan_rounds_kernel<<<1, PL_THREADS, 0, s>>>(A, W.cat_cnt, W.blk_cnt, W.cat_base, W.lst_n, W.lst_m, W.lst_first,
-                                              W.lst_base, W.grp_fill, W.grp_off, tb.fill_topk, tb.fill_total);
-  prof_end(K_PLAN, s);
   prof_begin(K_SCATTER_CAND, s);
-  scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_base, W.cand_key,
+  scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_cnt, W.cand_key,
                                                        W.cand_tok);
   prof_end(K_SCATTER_CAND, s);
   prof_begin(K_SELECT_SLOT, s);
-  select_slot_kernel<<<D.NL, SS_THREADS, 0, s>>>(A, W.lst_n, W.lst_m, W.lst_first, W.lst_base, W.cand_key, W.cand_tok,
-                                                 tb.slot, tb.slot_token);
+  select_slot_kernel<<<D.NL, SS_THREADS, 0, s>>>(A, W.cat_cnt, W.blk_cnt, W.cand_key, W.cand_tok, tb.slot,
+                                                 tb.slot_token, W.grp_fill, W.grp_off, tb.fill_topk, tb.fill_total);
   prof_end(K_SELECT_SLOT, s);
   if (D.ir) {
     prof_begin(K_IR_COUNT, s);
@@ -654,11 +662,9 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     scan_blocks_kernel<<<D.E, SC_THREADS, 0, s>>>(W.ir_blk_cnt, W.ir_cnt, D.NB);
     prof_end(K_IR_SCAN, s);
   }
-  prof_begin(K_ROW_PLAN, s);
-  row_plan_kernel<<<1, 64, 0, s>>>(A, tb.fill_total, W.ir_cnt, tb.ir_offset, W.row_base, W.tiles, W.tile_ctl);
-  prof_end(K_ROW_PLAN, s);
   prof_begin(K_IR_WEIGHTS, s);
-  ir_weights_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.key, W.ir_score, W.ir_cand, W.ir_blk_cnt, tb.ir_offset,
+  ir_weights_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.key, W.ir_score, W.ir_cand, W.ir_blk_cnt, W.ir_cnt,
+                                               tb.fill_total, tb.ir_offset, W.row_base, W.tiles, W.tile_ctl,
                                                tb.ir_expert, tb.ir_row, tb.ir_token, tb.combine_w);
   prof_end(K_IR_WEIGHTS, s);
   if (D.quota && D.max_mtiles > 0)  // the forward pass addresses dispatched rows through row_token

@@ -3,7 +3,7 @@
 //          h[row, f] = gelu(x[row] . W1_e[f])                            (GELU)
 //   down : y[row, c] = h[row] . W2_e[c]
 // Both are "A[rows,K] times B[N,K]^T" with K contiguous in both operands.  Rows of expert e are
-// row_base[e] .. row_base[e+1]-1 and are cut into row tiles by row_plan (TileInfo).
+// row_base[e] .. row_base[e+1]-1 and are cut into row tiles when the routing tables are built (TileInfo).
 //
 // bf16 main path (K % 64 == 0): persistent kernel, one workgroup of 8 waves per CU, tiles of 256 x
 // 256 staged rows dealt round-robin.

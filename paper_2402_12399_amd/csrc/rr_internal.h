@@ -51,11 +51,6 @@ struct Work {
   int32_t *ir_cand;      // [T]       that expert
   int32_t *blk_cnt;      // [NCAT, NB] candidates per (list, token block); scanned in place
   int32_t *cat_cnt;      // [NCAT]    candidates per (round, expert)
-  int32_t *cat_base;     // [NCAT]    start of that candidate array in cand_*
-  int32_t *lst_n;        // [NL]      candidates of a selection list (a contiguous piece of a candidate array)
-  int32_t *lst_m;        // [NL]      how many of them are kept
-  int32_t *lst_first;    // [NL]      slot of the first kept one (block start + slots occupied by earlier rounds)
-  int32_t *lst_base;     // [NL]      start of the list in cand_*
   int32_t *grp_fill;     // [E, Gq]   occupied slots of each capacity block after the last round
   int32_t *grp_off;      // [E, Gq]   occupied slots of the expert's earlier blocks (its dispatched rows skip the holes)
   int32_t *row_token;    // [Rmax]    per-group quotas only: token of every dispatched row
@@ -80,8 +75,8 @@ struct Launch {
 
 // Kernel ids for the profiling record.
 enum KernelId {
-  K_ROUTER = 0, K_TOPK, K_SCAN_CAND, K_PLAN, K_SCATTER_CAND, K_SELECT_SLOT,
-  K_IR_COUNT, K_IR_SCAN, K_ROW_PLAN, K_IR_WEIGHTS, K_GATHER, K_FFN_UP, K_FFN_DOWN, K_COMBINE,
+  K_ROUTER = 0, K_TOPK, K_SCAN_CAND, K_SCATTER_CAND, K_SELECT_SLOT,
+  K_IR_COUNT, K_IR_SCAN, K_IR_WEIGHTS, K_GATHER, K_FFN_UP, K_FFN_DOWN, K_COMBINE,
   K_COUNT
 };
 

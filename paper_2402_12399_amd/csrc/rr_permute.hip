@@ -1,7 +1,7 @@
 // Dispatch gather and weighted combine: on one GPU the expert-parallel all-to-all of Sec. 3 is a
 // row permutation in device memory.
 //
-// Dispatched-row layout (built by row_plan): expert e owns rows [row_base[e], row_base[e+1]): its
+// Dispatched-row layout (built with the routing tables): expert e owns rows [row_base[e], row_base[e+1]): its
 // occupied capacity slots in slot order, then its Intra-GPU list.  Padding slots get no row:
 // FFN(0) = 0 contributes nothing (Sec. 3, zero padding).  Slot s of capacity block g = s / Cq is
 // row row_base[e] + grp_off[e, g] + s % Cq, where grp_off counts the occupied slots of the expert's
