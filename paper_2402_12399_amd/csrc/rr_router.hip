@@ -436,9 +436,22 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
     }
     __builtin_amdgcn_wave_barrier();
     // logits rows of the fragment are contiguous in memory
-    for (int idx = lane; idx < ntok * E; idx += kWave) {
-      const int row = idx / E, e = idx - row * E;
-      logits[(size_t)tf0 * E + idx] = tile[row * TSTR + e];
+    if (EXACT) {
+      // E == ROWS: a lane stores four consecutive experts of a token, a wave 1 KB per instruction
+      constexpr int LPR = ROWS / 4;  // lanes per row
+      const int r0 = lane / LPR, e0 = (lane % LPR) * 4;
+#pragma unroll
+      for (int it = 0; it < 32 / (kWave / LPR); ++it) {
+        const int row = it * (kWave / LPR) + r0;
+        const float *src = tile + row * TSTR + e0;
+        if (row < ntok)
+          *reinterpret_cast<float4 *>(logits + (size_t)(tf0 + row) * ROWS + e0) = make_float4(src[0], src[1], src[2], src[3]);
+      }
+    } else {
+      for (int idx = lane; idx < ntok * E; idx += kWave) {
+        const int row = idx / E, e = idx - row * E;
+        logits[(size_t)tf0 * E + idx] = tile[row * TSTR + e];
+      }
     }
     if (lane < ntok) {
       const float *row = tile + lane * TSTR;
