@@ -82,6 +82,8 @@ static int make_dims(const rr_config *c, bool need_ffn, Dims *D) {
   D->NCAT = D->NR * c->E;
   D->NL = D->NCAT * Gq;
   D->NB = (c->T + kTokBlock - 1) / kTokBlock;
+  D->cb = 1;
+  D->NBc = D->NB;
   D->dtype = c->dtype; D->act = c->act;
   int64_t slots = (int64_t)C * c->E, assigns = (int64_t)D->NR * c->T;
   int64_t rmax = (slots < assigns ? slots : assigns) + (D->ir ? c->T : 0);
@@ -109,7 +111,7 @@ static size_t carve(const Dims &D, bool forward, void *ws, Work *W) {
   W->key = cv.take<u32>(T * NR);
   W->ir_score = cv.take<float>(T);
   W->ir_cand = cv.take<int32_t>(T);
-  W->blk_cnt = cv.take<int32_t>((size_t)D.NCAT * D.NB);
+  W->blk_cnt = cv.take<int32_t>((size_t)D.NCAT * D.NB * router_count_blocks(D));
   W->cat_cnt = cv.take<int32_t>(D.NCAT);
   W->grp_fill = cv.take<int32_t>(E * D.Gq);
   W->grp_off = cv.take<int32_t>(E * D.Gq);
@@ -233,8 +235,10 @@ int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, c
   hipStream_t s = static_cast<hipStream_t>(stream);
   const rr_tables &tb = tables ? *tables : W.tables;
   float *lg = logits ? logits : W.logits;
+  D.cb = router_count_blocks(D);  // the router ranks and counts: per 32 tokens for small batches
+  D.NBc = (D.T + kTokBlock / D.cb - 1) / (kTokBlock / D.cb);
   hipError_t e = launch_router(D, x, w_router, bias, lg, nullptr, nullptr, &tb, &W, s);
-  if (e == hipSuccess) e = launch_dispatch(D, lg, tb, W, router_ranks(D), s);
+  if (e == hipSuccess) e = launch_dispatch(D, lg, tb, W, true, s);
   if (routing_only) return e == hipSuccess ? RR_OK : RR_ERR_HIP;
   if (e == hipSuccess && !ffn_fuses_gather(D)) e = launch_gather(D, x, tb, W, s);
   if (e == hipSuccess) e = launch_ffn(D, x, tb, w1, w3, w2, W, s);

@@ -31,6 +31,7 @@ constexpr int TS = kMaxE + 1;  // LDS row stride of a [token][expert] tile
 struct DispatchArgs {
   int T, E, k, C, NR, NCAT, NB, Eg, Tg, ir, fr, arrival, BM, max_mtiles;
   int Cq, Gq, NL;  // capacity blocks: Gq per expert (1, or one per group with per-group quotas) of Cq slots
+  int NBc, cb;     // candidate counts come per count block: cb of them per token block, NBc in all
 };
 
 // lanes of this wave whose (valid, e) equals the caller's; e < 64
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(kTokBlock) void topk_rank_kernel(const float *__res
     ir_cand[i] = arg;
   }
   __syncthreads();
-  for (int c = tid; c < A.NCAT; c += kTokBlock) blk_cnt[(size_t)c * A.NB + b] = cnt[c];
+  for (int c = tid; c < A.NCAT; c += kTokBlock) blk_cnt[(size_t)c * A.NBc + b] = cnt[c];  // here cb == 1
 }
 
 // ------------------------------------------------------------------ scan over token blocks
@@ -222,7 +223,7 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
   for (int r = 0; r < kMaxRounds; ++r) {
     if (r < A.NR) {
       int e = e_r[r], cat = r * A.E + e;
-      int pos = s_base[cat] + blk_off[(size_t)cat * A.NB + b] + rank_r[r];
+      int pos = s_base[cat] + blk_off[(size_t)cat * A.NBc + b * A.cb] + rank_r[r];
       for (int q = 0; q < w; ++q) pos += wcnt[r][q][e];
       cand_key[pos] = key[(size_t)i * A.NR + r];
       cand_tok[pos] = i;
@@ -305,12 +306,12 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
   // list = (round r, expert j, capacity block g); n candidates, m of them kept, in slots fill0 ..
   const int lst = blockIdx.x, cat = lst / A.Gq, g = lst - cat * A.Gq, r = cat / A.E, j = cat - r * A.E;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int bpg = A.NB / A.Gq;  // token blocks per group (exact with quotas; all of them otherwise)
+  const int bpg = A.NB / A.Gq * A.cb;  // count blocks per group (exact with quotas; all of them otherwise)
   // candidates [lo, hi) of (round rr, expert j) that belong to group gg
   auto piece = [&](int rr, int gg, int &lo, int &hi) {
     const int c = rr * A.E + j;
-    lo = gg == 0 ? 0 : blk_off[(size_t)c * A.NB + gg * bpg];
-    hi = gg == A.Gq - 1 ? cat_cnt[c] : blk_off[(size_t)c * A.NB + (gg + 1) * bpg];
+    lo = gg == 0 ? 0 : blk_off[(size_t)c * A.NBc + gg * bpg];
+    hi = gg == A.Gq - 1 ? cat_cnt[c] : blk_off[(size_t)c * A.NBc + (gg + 1) * bpg];
   };
   int n = 0, m = 0, fill = 0, lo = 0;
   for (int rr = 0; rr <= r; ++rr) {
@@ -636,7 +637,7 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
 hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, bool ranked,
                            hipStream_t s) {
   DispatchArgs A{D.T, D.E, D.k, D.C, D.NR, D.NCAT, D.NB, D.Eg, D.Tg, D.ir, D.fr, D.arrival, D.BM, D.max_mtiles,
-                 D.Cq, D.Gq, D.NL};
+                 D.Cq, D.Gq, D.NL, D.NBc, D.cb};
   if (!ranked) {  // otherwise the router's epilogue has already written what topk_rank writes
     prof_begin(K_TOPK, s);
     topk_rank_kernel<<<D.NB, kTokBlock, 0, s>>>(logits, A, tb.rank_expert, tb.slot, W.key, W.ir_score, W.ir_cand,
@@ -644,7 +645,7 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     prof_end(K_TOPK, s);
   }
   prof_begin(K_SCAN_CAND, s);
-  scan_blocks_kernel<<<D.NCAT, SC_THREADS, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NB);
+  scan_blocks_kernel<<<D.NCAT, SC_THREADS, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NBc);
   prof_end(K_SCAN_CAND, s);
   prof_begin(K_SCATTER_CAND, s);
   scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_cnt, W.cand_key,

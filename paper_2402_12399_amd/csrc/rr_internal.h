@@ -29,6 +29,8 @@ struct Dims {
   int NCAT;    // NR * E candidate arrays (one per round and expert, ascending token index)
   int NL;      // NCAT * Gq selection lists: list id = (round * E + expert) * Gq + block
   int NB;      // token blocks of kTokBlock
+  int cb;      // candidate-count blocks per token block (1, or 4 when the small-batch router counts per 32 tokens)
+  int NBc;     // candidate-count blocks: blk_cnt is [NCAT, NBc]
   int ir, fr, arrival;
   int dtype, act;
   int Rmax;        // upper bound on dispatched rows: min(E*C, NR*T) + (ir ? T : 0)
@@ -49,7 +51,7 @@ struct Work {
   u32     *key;          // [T, NR]   order-preserving key of the score of the r-th choice
   float   *ir_score;     // [T]       score of the best expert of the token's own group
   int32_t *ir_cand;      // [T]       that expert
-  int32_t *blk_cnt;      // [NCAT, NB] candidates per (list, token block); scanned in place
+  int32_t *blk_cnt;      // [NCAT, NBc] candidates per (list, count block); scanned in place
   int32_t *cat_cnt;      // [NCAT]    candidates per (round, expert)
   int32_t *grp_fill;     // [E, Gq]   occupied slots of each capacity block after the last round
   int32_t *grp_off;      // [E, Gq]   occupied slots of the expert's earlier blocks (its dispatched rows skip the holes)
@@ -96,8 +98,9 @@ __host__ __device__ inline float key_score(u32 key) {
 
 // Stage launchers (each returns a hipError_t from the launches it made).
 // With tb and W the router may also do the per-token ranking that the routing tables start from
-// (router_ranks(D) says whether it does); launch_dispatch is then told to skip that step.
-bool router_ranks(const Dims &D);
+// and launch_dispatch is told to skip that step.  The small-batch router counts candidates per 32
+// tokens (its workgroup), the others per token block: router_count_blocks(D) = count blocks per token block.
+int router_count_blocks(const Dims &D);
 hipError_t launch_router(const Dims &D, const void *x, const float *w_router, const float *bias,
                          float *logits, float *probs, int32_t *rank_expert, const rr_tables *tb, const Work *W,
                          hipStream_t s);

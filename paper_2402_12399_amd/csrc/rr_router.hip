@@ -87,18 +87,59 @@ __device__ inline f32x16 mfma5(const Frag &xh, const Frag &xl, const Frag &wh, c
   return acc;
 }
 
-template <bool BF16, int TM, int NJ>
+struct RankOut {
+  int32_t *rank_expert, *slot;  // [T,k+1]
+  u32 *key;                     // [T,NR]
+  float *ir_score;              // [T]
+  int32_t *ir_cand;             // [T]
+  int32_t *blk_cnt;             // [NCAT, NBc]
+  int k, NR, fr, Eg, Tg, NCAT, NBc;
+};
+
+// One lane ranks one token from its finished row of logits (LDS): the top-(k+1) experts; with FUSE
+// also what the routing tables start from - score keys, the candidate counts of the token's count
+// block (LDS atomics on cnt[round * E + expert]), the best expert of the token's own group
+// (Sec. 4.1) - so that the logits are not read back from HBM.
+template <bool FUSE>
+__device__ inline void rank_row(const float *row, int tok, int E, int k, int32_t *rank_expert, const RankOut &R,
+                                int *cnt) {
+  float bs[kMaxRank];
+  int be[kMaxRank];
+  const int n = min(k + 1, E);
+  top_n_of_row(row, E, n, bs, be);
+  int32_t *ranks = FUSE ? R.rank_expert : rank_expert;
+#pragma unroll
+  for (int q = 0; q < kMaxRank; ++q) {
+    if (q <= k) ranks[(size_t)tok * (k + 1) + q] = (q < n) ? be[q] : -1;
+    if (FUSE && q < R.NR) {
+      R.key[(size_t)tok * R.NR + q] = score_key(bs[q]);
+      atomicAdd(&cnt[q * E + be[q]], 1);
+    }
+  }
+  if (FUSE) {
+    if (!R.fr) R.slot[(size_t)tok * (k + 1) + k] = -1;
+    const int g = tok / R.Tg;
+    float best;
+    int arg;
+    best_in_group(row, g * R.Eg, (g + 1) * R.Eg, best, arg);
+    R.ir_score[tok] = best;
+    R.ir_cand[tok] = arg;
+  }
+}
+
+template <bool BF16, int TM, int NJ, bool FUSE>
 __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restrict__ xv, const float *__restrict__ wr,
                                                             const float *__restrict__ bias, float *__restrict__ logits,
                                                             float *__restrict__ probs, int32_t *__restrict__ rank_expert,
-                                                            int T, int d, int E, int k) {
-  constexpr int TB = TM * 32;                 // tokens per workgroup
+                                                            int T, int d, int E, int k, RankOut R) {
+  constexpr int TB = TM * 32;                 // tokens per workgroup = one candidate-count block (FUSE)
   constexpr int S = BF16 ? 32 : 16;           // elements in a lane's 64-byte segment
   constexpr int KM = 2 * S;                   // K advance per macro-step
   constexpr int MS = S / 8;                   // MFMA k-steps per macro-step
   constexpr int ES = BF16 ? 2 : 4;
   __shared__ float red[RT_NW][TB * RT_TS];
   __shared__ float row_max[TB], row_inv[TB];
+  __shared__ int cnt[kMaxRounds * kMaxE];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int fr = lane & 31, fh = lane >> 5;
   const int t0 = blockIdx.x * TB;
@@ -200,6 +241,8 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
     const int o = row * RT_TS + e;
     tile[o] = ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + (bias ? bias[e] : 0.0f);
   }
+  if (FUSE)
+    for (int c = tid; c < R.NCAT; c += RT_THREADS) cnt[c] = 0;
   __syncthreads();
 
   const int ntok = min(TB, T - t0);
@@ -218,23 +261,17 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
       row_max[tid] = m;
       row_inv[tid] = 1.0f / s;
     }
-    if (rank_expert) {
-      float bs[kMaxRank];
-      int be[kMaxRank];
-      int n = min(k + 1, E);
-      top_n_of_row(row, E, n, bs, be);
-#pragma unroll
-      for (int q = 0; q < kMaxRank; ++q)
-        if (q <= k) rank_expert[(size_t)(t0 + tid) * (k + 1) + q] = (q < n) ? be[q] : -1;
-    }
+    if (rank_expert || FUSE) rank_row<FUSE>(row, t0 + tid, E, k, rank_expert, R, cnt);
   }
+  if (probs || FUSE) __syncthreads();
   if (probs) {
-    __syncthreads();
     for (int idx = tid; idx < ntok * E; idx += RT_THREADS) {
       int row = idx / E, e = idx - row * E;
       probs[(size_t)t0 * E + idx] = expf(tile[row * RT_TS + e] - row_max[row]) * row_inv[row];
     }
   }
+  if (FUSE)
+    for (int c = tid; c < R.NCAT; c += RT_THREADS) R.blk_cnt[(size_t)c * R.NBc + blockIdx.x] = cnt[c];
 }
 
 // ------------------------------------------------------------------ large batches
@@ -245,16 +282,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
 // GEMM); x still streams global -> registers, one K chunk (64 bytes per lane) ahead.  One barrier
 // per chunk.
 // With a RankOut the epilogue also does the per-token work that the routing tables start from
-// (ranking, score keys, best expert of the token's own group, candidate counts per 128-token
-// block), so the logits are not read back from HBM.
-struct RankOut {
-  int32_t *rank_expert, *slot;  // [T,k+1]
-  u32 *key;                     // [T,NR]
-  float *ir_score;              // [T]
-  int32_t *ir_cand;             // [T]
-  int32_t *blk_cnt;             // [NCAT, NB]
-  int k, NR, fr, Eg, Tg, NCAT, NB;
-};
+// (see rank_row; candidate counts per 128-token block), so the logits are not read back from HBM.
 
 constexpr int RS_TM = 2;                     // 32-token fragments per wave
 constexpr int RS_TB = RT_NW * RS_TM * 32;    // 256 tokens per workgroup
@@ -464,30 +492,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
         row_max[w][lane] = mx;
         row_inv[w][lane] = 1.0f / sum;
       }
-      if (rank_expert || FUSE) {
-        float bs[kMaxRank];
-        int be[kMaxRank];
-        const int n = min(k + 1, E);
-        top_n_of_row(row, E, n, bs, be);
-        int32_t *ranks = FUSE ? R.rank_expert : rank_expert;
-#pragma unroll
-        for (int q = 0; q < kMaxRank; ++q) {
-          if (q <= k) ranks[(size_t)tok * (k + 1) + q] = (q < n) ? be[q] : -1;
-          if (FUSE && q < R.NR) {
-            R.key[(size_t)tok * R.NR + q] = score_key(bs[q]);
-            atomicAdd(&cnt[w >> 1][q * E + be[q]], 1);
-          }
-        }
-        if (FUSE) {
-          if (!R.fr) R.slot[(size_t)tok * (k + 1) + k] = -1;
-          const int g = tok / R.Tg;
-          float best;
-          int arg;
-          best_in_group(row, g * R.Eg, (g + 1) * R.Eg, best, arg);
-          R.ir_score[tok] = best;
-          R.ir_cand[tok] = arg;
-        }
-      }
+      if (rank_expert || FUSE) rank_row<FUSE>(row, tok, E, k, rank_expert, R, cnt[w >> 1]);
     }
     if (probs) {
       __builtin_amdgcn_wave_barrier();
@@ -503,19 +508,26 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
     // waves 0,1 cover token block 2*blockIdx.x, waves 2,3 the next one
     for (int c = tid; c < 2 * R.NCAT; c += RT_THREADS) {
       const int half = c / R.NCAT, cat = c - half * R.NCAT, b = 2 * blockIdx.x + half;
-      if (b < R.NB) R.blk_cnt[(size_t)cat * R.NB + b] = cnt[half][cat];
+      if (b < R.NBc) R.blk_cnt[(size_t)cat * R.NBc + b] = cnt[half][cat];
     }
   }
 }
 
+constexpr int RK_TM = 1;  // the small-batch kernel: 32 tokens per workgroup
+static_assert(kTokBlock % (RK_TM * 32) == 0, "count blocks must tile the token blocks");
+
 template <bool BF16, int TM>
 void launch_one(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits, float *probs,
-                int32_t *rank_expert, hipStream_t s) {
+                int32_t *rank_expert, const RankOut *R, hipStream_t s) {
   dim3 grid((D.T + TM * 32 - 1) / (TM * 32)), block(RT_THREADS);
-  if (D.E <= 32)
-    router_kernel<BF16, TM, 1><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k);
-  else
-    router_kernel<BF16, TM, 2><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k);
+  RankOut none{};
+  if (D.E <= 32) {
+    if (R) router_kernel<BF16, TM, 1, true><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k, *R);
+    else router_kernel<BF16, TM, 1, false><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k, none);
+  } else {
+    if (R) router_kernel<BF16, TM, 2, true><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k, *R);
+    else router_kernel<BF16, TM, 2, false><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k, none);
+  }
 }
 
 template <bool BF16>
@@ -542,22 +554,23 @@ void launch_stream(const Dims &D, const void *x, const float *w_router, const fl
 
 }  // namespace
 
-bool router_ranks(const Dims &D) { return D.T > 64 * 1024; }
+static bool router_small(const Dims &D) { return D.T <= 64 * 1024; }
+int router_count_blocks(const Dims &D) { return router_small(D) ? kTokBlock / (RK_TM * 32) : 1; }
 
 hipError_t launch_router(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits,
                          float *probs, int32_t *rank_expert, const rr_tables *tb, const Work *W, hipStream_t s) {
   // small batches: 32-token tiles with K split across the waves, so that the launch still fills the
   // chip; large ones: the streaming kernel
-  const bool small = !router_ranks(D);
+  const bool small = router_small(D);
   prof_begin(K_ROUTER, s);
+  RankOut R{};
+  if (tb && W)  // D.NBc is then the count-block grid of this router (see router_count_blocks)
+    R = RankOut{tb->rank_expert, tb->slot, W->key, W->ir_score, W->ir_cand, W->blk_cnt,
+                D.k, D.NR, D.fr, D.Eg, D.Tg, D.NCAT, D.NBc};
   if (small) {
-    if (D.dtype == RR_BF16) launch_one<true, 1>(D, x, w_router, bias, logits, probs, rank_expert, s);
-    else launch_one<false, 1>(D, x, w_router, bias, logits, probs, rank_expert, s);
+    if (D.dtype == RR_BF16) launch_one<true, RK_TM>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
+    else launch_one<false, RK_TM>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
   } else {
-    RankOut R{};
-    if (tb && W)
-      R = RankOut{tb->rank_expert, tb->slot, W->key, W->ir_score, W->ir_cand, W->blk_cnt,
-                  D.k, D.NR, D.fr, D.Eg, D.Tg, D.NCAT, D.NB};
     if (D.dtype == RR_BF16) launch_stream<true>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
     else launch_stream<false>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
   }
