@@ -42,7 +42,7 @@ def parse():
     ap.add_argument("--mode", default="ir+fr", help="vanilla | ir | fr | ir+fr")
     ap.add_argument("--quota", action="store_true",
                     help="capacity per group (RR_QUOTA_PER_GROUP) instead of one queue per expert over all tokens")
-    ap.add_argument("--cpu-sample", type=int, default=2048, help="tokens the CPU oracle computes outputs for (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle computes outputs for (0 = skip)")
     ap.add_argument("--no-extras", action="store_true",
                     help="only the headline workload: skip the paper-shape (c3) and routing-stress (c4) extras")
     ap.add_argument("--no-routing-stress", action="store_true",
