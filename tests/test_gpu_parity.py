@@ -342,6 +342,12 @@ def test_quota_forward_c1_fp32(mode):
 
 
 QUOTA_SMALL = [w for w in SMALL_BF16 if (w.T // w.G) * w.G == w.T and (w.T // w.G) % 128 == 0]
+QUOTA_SMALL += [
+    # bf16 shape that takes the register-staged GEMM and the separate gather kernel (d % 64 != 0), E not a power of two
+    wl.Workload("q1", 1024, 136, 264, 6, 2, 1, 0.5, "bf16", "swiglu", "zipf:1.5", 31),
+    # fp32 path (plain FMA GEMM), top-2, three groups
+    wl.Workload("q2", 1152, 72, 200, 6, 3, 2, 1.0, "f32", "swiglu", "normal:1.0", 32),
+]
 
 
 @pytest.mark.parametrize("w", QUOTA_SMALL, ids=[w.name for w in QUOTA_SMALL])
