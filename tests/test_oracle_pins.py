@@ -440,12 +440,11 @@ def test_ir_weight_scales_with_number_of_drops():
     assert t2["combine_w"][1].tolist() == pytest.approx(w(2.5, f32(0.2), 1), abs=1e-15)
     assert t2["combine_w"][2].tolist() == pytest.approx([1 / (1 + math.exp(-1)), 1 / (1 + math.exp(1)), 0, 0], abs=1e-15)
     assert t2["combine_w"][3].tolist() == [0.0, 0.0, 0.0, 1.0]
-    # a mixed case where the factor matters: t kept at a_j, dropped TWICE is impossible for k=2,
-    # so use k=3: one kept (a=1.0), two drops, local best a=0.0 -> weights e : 2
+    # A case where the factor k - |R_i| is 2 (needs k = 3: one choice kept, two dropped).
+    # T = 4, E = 4, G = 1, C = ceil(0.25 * 4 / 4) = 1.  Round 0: all four tokens choose e1, which keeps
+    # the best (t2 at 7.0, the lower index of the tie with t3); round 1: all four choose e2, which keeps
+    # t2 (6.0); round 2: t0 -> e0 (1.0) and t1 -> e0 (0.0): e0 keeps t0.
     a3 = np.array([[1.0, 5.0, 4.0, -9.0], [0.0, 6.0, 5.0, -9.0]] + [[-9.0, 7.0, 6.0, -9.0]] * 2, dtype=np.float32)
-    # T=4, E=4, G=1, C = ceil(0.25*4/4) = 1: e1 and e2 are taken by later tokens? no: round 0
-    # e1 <- all four, keeps the best (t2: 7.0, lowest index of the tie); round 1 e2 <- all four,
-    # keeps t2 (6.0); round 2: t0 -> e0 (1.0) kept alone; t1 -> e0 (0.0) loses to t0.
     t3 = orc.route(a3, 3, 1, 0.25, intra_gpu=True, fill_in=False)
     assert t3["C"] == 1 and t3["slot_token"].tolist() == [[0], [2], [2], [-1]]
     assert t3["n_drop"].tolist() == [2, 3, 1, 3]
