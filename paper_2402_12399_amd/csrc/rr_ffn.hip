@@ -5,12 +5,13 @@
 // Both are "A[rows,K] times B[N,K]^T" with K contiguous in both operands.  Rows of expert e are
 // row_base[e] .. row_base[e+1]-1 and are cut into row tiles when the routing tables are built (TileInfo).
 //
-// bf16 main path (K % 64 == 0): persistent kernel, one workgroup of 8 waves per CU, tiles of 256 x
-// 256 staged rows dealt round-robin.
+// bf16 main path (K % 64 == 0, K >= 192): persistent kernel, one workgroup of 8 waves per CU, tiles of
+// 256 x 256 staged rows dealt in an XCD-aware panel order (see "Tile order" in the kernel).
 //   * v_mfma_f32_32x32x16_bf16, fp32 accumulate; 2 x 4 waves, wave tile 128 x 64; two waves per SIMD
 //     so that one wave's LDS reads overlap the other's MFMAs.
-//   * K advances in chunks of 64 through two 64 KB LDS stages filled by buffer_load ... lds (16 bytes
-//     per lane straight into LDS, no staging registers).  A wave instruction fills 1 KB = 8
+//   * K advances in chunks of 64 through LDS rings - two 32 KB stages of A, three of B, 160 KB in all
+//     - filled by buffer_load ... lds (16 bytes per lane straight into LDS, no staging registers);
+//     the chunks of a workgroup's successive tiles form one stream.  A wave instruction fills 1 KB = 8
 //     consecutive LDS rows (lane l -> row l/8, chunk position l%8), so the swizzle is applied on the
 //     global side: the lane fetches the chunk that belongs at its position.  Rows past the end of
 //     an operand read as zero (buffer range check): ragged tiles need no masks on the load side.
