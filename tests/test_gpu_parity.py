@@ -205,6 +205,47 @@ def test_forward_is_deterministic():
         assert torch.equal(first.view(torch.int16), again.view(torch.int16))
 
 
+def test_forward_under_graph_capture():
+    """rr_moe_forward only enqueues kernels on the caller's stream (no allocation, no memset, no
+    synchronisation), so a caller may capture it in a HIP graph: every replay must give the eager bits,
+    also with eager calls and synchronisations in between."""
+    w = SMALL_BF16[0]
+    inputs = wl.make_inputs(w)
+    cfg = gu.config_of(w, ("ir", "fr"))
+    dev = {n: (torch.from_numpy(inputs[n]).cuda() if n in ("w_router", "bias") and inputs[n] is not None
+               else gu.to_device(inputs[n], w.dtype)) for n in ("x", "w_router", "bias", "w1", "w3", "w2")}
+    out = torch.empty((cfg.T, cfg.d_model), dtype=torch.bfloat16, device="cuda")
+    logits = torch.empty((cfg.T, cfg.E), dtype=torch.float32, device="cuda")
+    tb, ws = rr.alloc_tables(cfg), rr.alloc_workspace(cfg)
+
+    def step():
+        rr.rr_moe_forward(cfg, dev["x"], dev["w_router"], dev["bias"], dev["w1"], dev["w3"], dev["w2"], out, tb, logits, ws)
+
+    step()  # first call: one-time kernel attributes are set outside the capture
+    torch.cuda.synchronize()
+    want = out.clone()
+    want_slot = tb.slot.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for _ in range(3):
+        out.zero_()
+        tb.slot.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want.view(torch.int16))
+        assert torch.equal(tb.slot, want_slot)
+        step()
+        torch.cuda.synchronize()
+
+
 @pytest.mark.parametrize("mode", MODES, ids=["vanilla", "ir", "fr", "ir+fr"])
 def test_forward_c2_full_size(mode):
     _full_size_case(wl.C2, mode)
