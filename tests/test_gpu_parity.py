@@ -404,3 +404,72 @@ def test_quota_forward_c2_full_size(mode):
 
 def test_quota_forward_c5_full_size():
     _full_size_case(wl.C5, ("ir", "fr"), n_sample=512, quota=True)
+
+
+# ------------------------------------------------------------------ seeded random configurations
+def test_dispatch_random_configurations():
+    """Sixty seeded draws over the whole argument space of the routing tables (sizes, E, G, k, capacity
+    factor, rectification modes, drop policy, capacity scope, tie density): tables bit-exact."""
+    rng = np.random.default_rng(2024)
+    done = 0
+    while done < 60:
+        G = int(rng.choice([1, 2, 3, 4, 8]))
+        E = G * int(rng.integers(1, 64 // G + 1))
+        k = int(rng.integers(1, 5))
+        if k > E:
+            continue
+        quota = bool(rng.integers(0, 2))
+        if quota:
+            T = G * 128 * int(rng.integers(1, 12))
+        else:
+            T = G * int(rng.integers(1, 1500))
+        mode = MODES[int(rng.integers(0, 4))]
+        if "fr" in mode and k + 1 > E:
+            continue
+        cf = float(rng.choice([0.05, 0.3, 0.5, 0.75, 1.0, 1.25, 2.0, 4.0]))
+        arrival = bool(rng.integers(0, 2))
+        ties = bool(rng.integers(0, 2))
+        a = wl.synthetic_logits(T, E, seed=1000 + done, bias_std=float(rng.choice([0.0, 1.0, 3.0])), ties=ties)
+        cfg = rr.RRConfig(T, 64, 0, E, k, G, cf, rr.RR_F32, rr.RR_ACT_SWIGLU, gu.flags_of(mode, arrival, quota))
+        try:
+            gu.assert_tables_equal(gu.run_dispatch(cfg, a), _oracle_tables(a, cfg, mode, arrival, quota))
+        except AssertionError as err:
+            raise AssertionError(f"T={T} E={E} G={G} k={k} cf={cf} mode={mode} arrival={arrival} quota={quota} "
+                                 f"ties={ties}: {err}") from None
+        done += 1
+
+
+def test_routing_only_forward_random_configurations():
+    """The same through rr_moe_forward with d_ff = 0 (the router's fused ranking instead of topk_rank):
+    inputs are small dyadic rationals, so the logits are exact and the tables must match bit for bit."""
+    rng = np.random.default_rng(77)
+    done = 0
+    while done < 24:
+        G = int(rng.choice([1, 2, 4]))
+        E = G * int(rng.integers(1, 64 // G + 1))
+        k = int(rng.integers(1, 4))
+        if k + 1 > E:
+            continue
+        quota = bool(rng.integers(0, 2))
+        T = G * 128 * int(rng.integers(1, 10)) if quota else G * int(rng.integers(10, 1200))
+        d = 8 * int(rng.integers(2, 40))
+        dtype = "bf16" if rng.integers(0, 2) else "f32"
+        x = rng.integers(-3, 4, size=(T, d)).astype(np.float32) / np.float32(2.0)
+        wr = rng.integers(-4, 5, size=(E, d)).astype(np.float32) / np.float32(8.0)
+        b = rng.integers(-8, 9, size=E).astype(np.float32) / np.float32(4.0)
+        cf = float(rng.choice([0.3, 0.75, 1.0, 1.5]))
+        cfg = rr.RRConfig(T, d, 0, E, k, G, cf, rr.RR_F32 if dtype == "f32" else rr.RR_BF16, rr.RR_ACT_SWIGLU,
+                          gu.flags_of(("ir", "fr"), False, quota))
+        xs = wl._store(x, dtype)
+        tb, logits = rr.alloc_tables(cfg), torch.empty((T, E), dtype=torch.float32, device="cuda")
+        ws = rr.alloc_workspace(cfg)
+        rr.rr_moe_forward(cfg, gu.to_device(xs, dtype), torch.from_numpy(wr).cuda(), torch.from_numpy(b).cuda(),
+                          None, None, None, None, tb, logits, ws)
+        torch.cuda.synchronize()
+        a = orc.router_scores(wl.values_f32(xs, dtype), wr, b)
+        assert np.array_equal(logits.cpu().numpy(), a), (T, d, E, dtype)
+        try:
+            gu.assert_tables_equal(tb.to_host(), orc.route(a, k, G, cf, True, True, quota=quota))
+        except AssertionError as err:
+            raise AssertionError(f"T={T} d={d} E={E} G={G} k={k} cf={cf} {dtype} quota={quota}: {err}") from None
+        done += 1
