@@ -182,23 +182,38 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
       }
   };
 
-  if (kbeg < kend) load_x(kbeg, xr);
-  for (int kb = kbeg; kb < kend; kb += KM) {
-    if (kb + KM < kend) load_x(kb + KM, xn);
+  // w of a macro-step: per k-step 8 consecutive fp32 of row (expert) fr.  Fetched one macro-step
+  // ahead like x (the weights sit in L2, but an L2 round trip per macro-step is most of a small
+  // batch's run time when it is not hidden).
+  uint4 wc[MS][NJ][2], wnx[MS][NJ][2];
+  auto load_wm = [&](int kb, uint4 (&dst)[MS][NJ][2]) {
 #pragma unroll
     for (int m = 0; m < MS; ++m) {
-      // w fragments of this k-step: 8 consecutive fp32 of row (expert) fr, split into three parts
       const int kw = kb + fh * S + m * 8;
-      Frag wh[NJ], wl[NJ], wl2[NJ];
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        uint4 a = make_uint4(0, 0, 0, 0), b = a;
+        dst[m][j][0] = dst[m][j][1] = make_uint4(0, 0, 0, 0);
         if (wok[j] && kw < kend) {
-          a = *reinterpret_cast<const uint4 *>(wrow[j] + kw);
-          b = *reinterpret_cast<const uint4 *>(wrow[j] + kw + 4);
+          dst[m][j][0] = *reinterpret_cast<const uint4 *>(wrow[j] + kw);
+          dst[m][j][1] = *reinterpret_cast<const uint4 *>(wrow[j] + kw + 4);
         }
-        split3x8(a, b, wh[j], wl[j], wl2[j]);
       }
+    }
+  };
+  if (kbeg < kend) {
+    load_x(kbeg, xr);
+    load_wm(kbeg, wc);
+  }
+  for (int kb = kbeg; kb < kend; kb += KM) {
+    if (kb + KM < kend) {
+      load_x(kb + KM, xn);
+      load_wm(kb + KM, wnx);
+    }
+#pragma unroll
+    for (int m = 0; m < MS; ++m) {
+      Frag wh[NJ], wl[NJ], wl2[NJ];
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) split3x8(wc[m][j][0], wc[m][j][1], wh[j], wl[j], wl2[j]);
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
         if (BF16) {
@@ -222,6 +237,13 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int q = 0; q < 4; ++q) xr[i][q] = xn[i][q];
+#pragma unroll
+    for (int m = 0; m < MS; ++m)
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        wc[m][j][0] = wnx[m][j][0];
+        wc[m][j][1] = wnx[m][j][1];
+      }
   }
 
   // ---- partial tiles to LDS: accumulator element v is token 8*(v/4) + 4*(lane/32) + v%4, expert lane%32
