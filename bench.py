@@ -138,6 +138,8 @@ def run_forward(rr, wl, torch, w, mode, steps, warmup, quota=False):
            "dispatch_gather": 2 * R * d * es + 4 * R,
            "combine": (n_src + T) * d * es + T * (k + 2) * 4}
     hbm.update(dispatch_bytes(T, E, k, k + (1 if "fr" in mode else 0), C, ir_rows))
+    if "topk_rank" not in kernels:  # the router's epilogue did the ranking: its table writes count for the router
+        hbm["router_scores"] += hbm["topk_rank"] - 4 * T * E
     peak_tf = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
     per_kernel = {}
     for n, ms in kernels.items():
