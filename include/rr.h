@@ -73,8 +73,9 @@ typedef struct rr_config {
 } rr_config;
 
 /* Routing, rectification and dispatch tables.  All device pointers, caller-allocated, every one
- * required.  C = rr_slots_per_expert(cfg): rr_capacity(T, E, cf), or G Cq with RR_QUOTA_PER_GROUP.  Column r < k of the [T,k+1] tables is the token's r-th choice
- * (Eq. 1), column k its (k+1)-th choice, the Fill-in nomination (Sec. 4.2 stage 1; -1 if k == E). */
+ * required.  C = rr_slots_per_expert(cfg): rr_capacity(T, E, cf), or G Cq with RR_QUOTA_PER_GROUP.
+ * Column r < k of the [T,k+1] tables is the token's r-th choice (Eq. 1), column k its (k+1)-th
+ * choice, the Fill-in nomination (Sec. 4.2 stage 1; -1 if k == E). */
 typedef struct rr_tables {
   int32_t *rank_expert; /* [T,k+1] experts by descending score, ties -> lower expert index         */
   int32_t *slot;        /* [T,k+1] slot in that expert's queue, -1 = dropped / not filled in       */
