@@ -205,6 +205,22 @@ def test_forward_is_deterministic():
         assert torch.equal(first.view(torch.int16), again.view(torch.int16))
 
 
+def test_forward_with_internal_tables_and_logits():
+    """tables and logits are optional outputs of rr_moe_forward: without them the call keeps both in
+    its workspace and must produce the same bits."""
+    w = SMALL_BF16[4]
+    inputs = wl.make_inputs(w)
+    cfg = gu.config_of(w, ("ir", "fr"))
+    dev = {n: (torch.from_numpy(inputs[n]).cuda() if n in ("w_router", "bias") and inputs[n] is not None
+               else gu.to_device(inputs[n], w.dtype)) for n in ("x", "w_router", "bias", "w1", "w3", "w2")}
+    want, _, _ = gu.run_forward(cfg, dev)
+    out = torch.zeros_like(want)
+    ws = rr.alloc_workspace(cfg)
+    rr.rr_moe_forward(cfg, dev["x"], dev["w_router"], dev["bias"], dev["w1"], dev["w3"], dev["w2"], out, None, None, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), want.view(torch.int16))
+
+
 def test_forward_under_graph_capture():
     """rr_moe_forward only enqueues kernels on the caller's stream (no allocation, no memset, no
     synchronisation), so a caller may capture it in a HIP graph: every replay must give the eager bits,
