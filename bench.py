@@ -305,7 +305,8 @@ def main():
         paper_shape = {"workload": wl.C3.name, "mode": "top2+ir+fr", "ms_per_step": r3["ms_per_step"],
                        "tokens_per_s": r3["tokens_per_s"], "ffn_tflops": r3["ffn_tflops"],
                        "kernel_ms": r3["kernel_ms"], "kernel_roofline": r3["kernel_roofline"], "rows": r3["rows"]}
-    stress = None if (args.no_routing_stress or args.no_extras) else routing_stress(rr, wl, torch, args.steps, args.warmup)
+    stress = None if (args.no_routing_stress or args.no_extras) else routing_stress(rr, wl, torch, args.steps, args.warmup,
+                                                                                    cpu=args.cpu_sample > 0)
     if args.copy_probe:
         src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")  # 1 GiB read + 1 GiB written
         dst = torch.empty_like(src)
@@ -338,7 +339,7 @@ def main():
     return 0
 
 
-def routing_stress(rr, wl, torch, steps, warmup):
+def routing_stress(rr, wl, torch, steps, warmup, cpu=False):
     """Routing-only workload (1M fp32 tokens, 64 experts in 8 groups, top-2, capacity factor 0.75):
     rr_moe_forward with d_ff = 0, i.e. router scores through combine weights, the memory-bound part of the path."""
     w = wl.C4
@@ -376,7 +377,20 @@ def routing_stress(rr, wl, torch, steps, warmup):
     disp = [n for n in kernels if n != "router_scores"]
     disp_ms = sum(kernels[n] for n in disp)
     disp_bytes = sum(hbm.get(n, 0) for n in disp)
+    cpu_routing = None
+    if cpu:  # the oracle's router + routing tables on the first 65536 tokens of the same x (same E, G, k, CF)
+        from oracle import rectify_router as orc
+        n = 65536
+        xs = dev["x"][:n].cpu().numpy()
+        wr = dev["w_router"].cpu().numpy()
+        t0 = time.perf_counter()
+        a = orc.router_scores(xs, wr, None)
+        orc.route(a, w.k, w.G, w.capacity_factor, True, True)
+        dt = time.perf_counter() - t0
+        cpu_routing = {"value": n / dt / 1e6, "unit": "Mtokens/s", "kind": "oracle",
+                       "sample": "router scores and routing tables of the first %d tokens (%.2f s)" % (n, dt)}
     return {"workload": w.name, "ms_per_step": ms, "mtokens_per_s": w.T / (ms * 1e-3) / 1e6,
+            "cpu_baseline": cpu_routing,
             "kernel_ms": {n: round(v, 5) for n, v in kernels.items()},
             "kernel_roofline": hbm_rooflines(kernels, hbm),
             "dispatch_roofline": {"bound": "hbm", "achieved": round(disp_bytes / (disp_ms * 1e-3) / 1e9, 1),
