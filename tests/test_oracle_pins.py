@@ -635,3 +635,87 @@ def test_quota_brute_force_and_invariants(seed):
             assert t["ir_expert"][i] == best
     sums = t["combine_w"].sum(axis=1)
     assert np.all(np.abs(sums - 1) < 1e-14)
+
+
+# ---------------------------------------------------------------- relabelling (metamorphic) pins
+def _kept_pairs(t, k):
+    """set of (token, expert, column) that hold a slot, and (token, expert) Intra-GPU assignments"""
+    T = t["slot"].shape[0]
+    kept = {(i, int(t["rank_expert"][i, r]), r) for i in range(T) for r in range(k + 1) if t["slot"][i, r] >= 0}
+    ir = {(i, int(t["ir_expert"][i])) for i in range(T) if t["ir_expert"][i] >= 0}
+    return kept, ir
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_relabelling_experts_relabels_the_tables(seed):
+    """With distinct scores nothing depends on expert numbers except through the group an expert is in:
+    a relabelling that keeps every expert in its group maps kept sets, weights and outputs onto each other."""
+    rng = np.random.default_rng(900 + seed)
+    T, E, G, k, d, F = 48, 8, 2, 2, 6, 10
+    a = rng.standard_normal((T, E)).astype(np.float32)
+    Eg = E // G
+    perm = np.concatenate([g * Eg + rng.permutation(Eg) for g in range(G)])  # new label of expert j is perm[j]
+    a2 = np.empty_like(a)
+    a2[:, perm] = a
+    t1 = orc.route(a, k, G, 0.75, True, True)
+    t2 = orc.route(a2, k, G, 0.75, True, True)
+    k1, ir1 = _kept_pairs(t1, k)
+    k2, ir2 = _kept_pairs(t2, k)
+    assert {(i, int(perm[e]), r) for (i, e, r) in k1} == k2
+    assert {(i, int(perm[e])) for (i, e) in ir1} == ir2
+    assert np.allclose(t1["combine_w"], t2["combine_w"], atol=1e-15)
+    assert np.array_equal(t1["fill_total"], t2["fill_total"][perm])
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    w1 = rng.standard_normal((E, F, d)).astype(np.float32)
+    w3 = rng.standard_normal((E, F, d)).astype(np.float32)
+    w2 = rng.standard_normal((E, d, F)).astype(np.float32)
+    inv = np.argsort(perm)  # weights of new expert j are those of old expert inv[j]
+    o1 = orc.moe_output(x, t1, k, w1, w3, w2, "swiglu")
+    o2 = orc.moe_output(x, t2, k, w1[inv], w3[inv], w2[inv], "swiglu")
+    assert np.allclose(o1, o2, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_relabelling_tokens_relabels_the_tables(seed):
+    """With distinct scores token numbers only matter through the group a token is in (and the order of
+    slots inside a round): a relabelling inside the groups maps kept sets and outputs onto each other."""
+    rng = np.random.default_rng(950 + seed)
+    T, E, G, k, d, F = 40, 6, 2, 1, 5, 7
+    a = rng.standard_normal((T, E)).astype(np.float32)
+    Tg = T // G
+    perm = np.concatenate([g * Tg + rng.permutation(Tg) for g in range(G)])  # new index of token i is perm[i]
+    a2 = np.empty_like(a)
+    a2[perm] = a
+    for quota in (False, True):
+        t1 = orc.route(a, k, G, 0.6, True, True, quota=quota)
+        t2 = orc.route(a2, k, G, 0.6, True, True, quota=quota)
+        k1, ir1 = _kept_pairs(t1, k)
+        k2, ir2 = _kept_pairs(t2, k)
+        assert {(int(perm[i]), e, r) for (i, e, r) in k1} == k2
+        assert {(int(perm[i]), e) for (i, e) in ir1} == ir2
+        assert np.allclose(t1["combine_w"], t2["combine_w"][perm], atol=1e-15)
+        x = rng.standard_normal((T, d)).astype(np.float32)
+        w1 = rng.standard_normal((E, F, d)).astype(np.float32)
+        w2 = rng.standard_normal((E, d, F)).astype(np.float32)
+        x2 = np.empty_like(x)
+        x2[perm] = x
+        o1 = orc.moe_output(x, t1, k, w1, None, w2, "gelu")
+        o2 = orc.moe_output(x2, t2, k, w1, None, w2, "gelu")
+        assert np.allclose(o1, o2[perm], rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_more_capacity_never_drops_more(seed):
+    """The kept set of the top-k rounds grows with the capacity factor (Sec. 5.3 reads its tables this way):
+    every assignment kept at a smaller capacity is kept at a larger one."""
+    rng = np.random.default_rng(980 + seed)
+    T, E, k = 64, 8, 2
+    a = rng.standard_normal((T, E)).astype(np.float32) + rng.standard_normal(E).astype(np.float32)
+    prev = None
+    for cf in (0.25, 0.5, 0.75, 1.0, 1.5, 2.0, 4.0, float(E)):
+        t = orc.route(a, k, 2, cf, False, False)
+        kept = {(i, r) for i in range(T) for r in range(k) if t["slot"][i, r] >= 0}
+        if prev is not None:
+            assert prev <= kept
+        prev = kept
+    assert len(prev) == T * k  # capacity factor E: every queue holds all T tokens
