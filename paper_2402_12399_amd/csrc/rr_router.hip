@@ -137,7 +137,8 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
   constexpr int KM = 2 * S;                   // K advance per macro-step
   constexpr int MS = S / 8;                   // MFMA k-steps per macro-step
   constexpr int ES = BF16 ? 2 : 4;
-  __shared__ float red[RT_NW][TB * RT_TS];
+  constexpr int TS = NJ * 32 + 1;             // LDS row stride of a [token][expert] tile
+  __shared__ float red[RT_NW][TB * TS];
   __shared__ float row_max[TB], row_inv[TB];
   __shared__ int cnt[kMaxRounds * kMaxE];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -254,13 +255,13 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        mine[(i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3)) * RT_TS + j * 32 + fr] = acc[i][j][v];
+        mine[(i * 32 + 8 * (v >> 2) + 4 * fh + (v & 3)) * TS + j * 32 + fr] = acc[i][j][v];
   __syncthreads();
   // ---- fixed-order sum of the four K slices, plus bias
   float *tile = red[0];
   for (int idx = tid; idx < TB * E; idx += RT_THREADS) {
     const int row = idx / E, e = idx - row * E;
-    const int o = row * RT_TS + e;
+    const int o = row * TS + e;
     tile[o] = ((red[0][o] + red[1][o]) + (red[2][o] + red[3][o])) + (bias ? bias[e] : 0.0f);
   }
   if (FUSE)
@@ -271,10 +272,10 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
   // logits rows of this tile are contiguous in memory
   for (int idx = tid; idx < ntok * E; idx += RT_THREADS) {
     int row = idx / E, e = idx - row * E;
-    logits[(size_t)t0 * E + idx] = tile[row * RT_TS + e];
+    logits[(size_t)t0 * E + idx] = tile[row * TS + e];
   }
   if (tid < ntok) {
-    const float *row = tile + tid * RT_TS;
+    const float *row = tile + tid * TS;
     if (probs) {
       float m = row[0];
       for (int e = 1; e < E; ++e) m = fmaxf(m, row[e]);
@@ -289,7 +290,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
   if (probs) {
     for (int idx = tid; idx < ntok * E; idx += RT_THREADS) {
       int row = idx / E, e = idx - row * E;
-      probs[(size_t)t0 * E + idx] = expf(tile[row * RT_TS + e] - row_max[row]) * row_inv[row];
+      probs[(size_t)t0 * E + idx] = expf(tile[row * TS + e] - row_max[row]) * row_inv[row];
     }
   }
   if (FUSE)
@@ -535,8 +536,10 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
   }
 }
 
-constexpr int RK_TM = 1;  // the small-batch kernel: 32 tokens per workgroup
-static_assert(kTokBlock % (RK_TM * 32) == 0, "count blocks must tile the token blocks");
+// Tokens per workgroup of the K-split kernel, in 32-token fragments: one for small batches, so that the
+// launch still fills the chip; two from 16 K tokens on (twice the reuse of every weight fragment), while
+// the partial tiles fit LDS (up to 32 experts).
+static int router_tm(const Dims &D) { return D.T > 16 * 1024 && D.E <= 32 ? 2 : 1; }
 
 template <bool BF16, int TM>
 void launch_one(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits, float *probs,
@@ -546,7 +549,7 @@ void launch_one(const Dims &D, const void *x, const float *w_router, const float
   if (D.E <= 32) {
     if (R) router_kernel<BF16, TM, 1, true><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k, *R);
     else router_kernel<BF16, TM, 1, false><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k, none);
-  } else {
+  } else if constexpr (TM == 1) {  // two column fragments: the partial tiles of two token fragments would not fit LDS
     if (R) router_kernel<BF16, TM, 2, true><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k, *R);
     else router_kernel<BF16, TM, 2, false><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs, rank_expert, D.T, D.d, D.E, D.k, none);
   }
@@ -577,7 +580,7 @@ void launch_stream(const Dims &D, const void *x, const float *w_router, const fl
 }  // namespace
 
 static bool router_small(const Dims &D) { return D.T <= 64 * 1024; }
-int router_count_blocks(const Dims &D) { return router_small(D) ? kTokBlock / (RK_TM * 32) : 1; }
+int router_count_blocks(const Dims &D) { return router_small(D) ? kTokBlock / (router_tm(D) * 32) : 1; }
 
 hipError_t launch_router(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits,
                          float *probs, int32_t *rank_expert, const rr_tables *tb, const Work *W, hipStream_t s) {
@@ -590,8 +593,14 @@ hipError_t launch_router(const Dims &D, const void *x, const float *w_router, co
     R = RankOut{tb->rank_expert, tb->slot, W->key, W->ir_score, W->ir_cand, W->blk_cnt,
                 D.k, D.NR, D.fr, D.Eg, D.Tg, D.NCAT, D.NBc};
   if (small) {
-    if (D.dtype == RR_BF16) launch_one<true, RK_TM>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
-    else launch_one<false, RK_TM>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
+    const RankOut *Rp = tb && W ? &R : nullptr;
+    if (router_tm(D) == 2) {
+      if (D.dtype == RR_BF16) launch_one<true, 2>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
+      else launch_one<false, 2>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
+    } else {
+      if (D.dtype == RR_BF16) launch_one<true, 1>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
+      else launch_one<false, 1>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
+    }
   } else {
     if (D.dtype == RR_BF16) launch_stream<true>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
     else launch_stream<false>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);

@@ -328,6 +328,37 @@ def test_routing_only_forward_large_batch(dtype, E, k, G):
     assert np.abs(probs.cpu().numpy() - orc.softmax_probs(a)).max() <= 1e-6
 
 
+@pytest.mark.parametrize("dtype,E,k,G,quota", [("bf16", 32, 1, 8, False), ("f32", 16, 2, 4, True), ("bf16", 24, 3, 2, False)])
+def test_routing_only_forward_mid_batch(dtype, E, k, G, quota):
+    """Between 16 K and 64 K tokens and up to 32 experts the K-split router takes 64 tokens per workgroup
+    (candidate counts per 64 tokens).  Exact dyadic inputs: logits and tables must match bit for bit."""
+    T, d = (20480 if quota else 20000 + 8 * G), 136
+    rng = np.random.default_rng(3 * E + k)
+    x = rng.integers(-3, 4, size=(T, d)).astype(np.float32) / np.float32(2.0)
+    wr = rng.integers(-4, 5, size=(E, d)).astype(np.float32) / np.float32(8.0)
+    b = rng.integers(-8, 9, size=E).astype(np.float32) / np.float32(4.0)
+    cfg = rr.RRConfig(T, d, 0, E, k, G, 0.75, rr.RR_F32 if dtype == "f32" else rr.RR_BF16, rr.RR_ACT_SWIGLU,
+                      gu.flags_of(("ir", "fr"), False, quota))
+    xs = wl._store(x, dtype)
+    tb, logits = rr.alloc_tables(cfg), torch.empty((T, E), dtype=torch.float32, device="cuda")
+    ws = rr.alloc_workspace(cfg)
+    rr.rr_moe_forward(cfg, gu.to_device(xs, dtype), torch.from_numpy(wr).cuda(), torch.from_numpy(b).cuda(),
+                      None, None, None, None, tb, logits, ws)
+    torch.cuda.synchronize()
+    a = orc.router_scores(wl.values_f32(xs, dtype), wr, b)
+    assert np.array_equal(logits.cpu().numpy(), a)
+    gu.assert_tables_equal(tb.to_host(), orc.route(a, k, G, 0.75, True, True, quota=quota))
+    # the stand-alone entry point takes the same kernel without the fused ranking
+    probs = torch.empty_like(logits)
+    ranks = torch.empty((T, k + 1), dtype=torch.int32, device="cuda")
+    rr.rr_router_scores(cfg, gu.to_device(xs, dtype), torch.from_numpy(wr).cuda(), torch.from_numpy(b).cuda(),
+                        logits, probs, ranks)
+    torch.cuda.synchronize()
+    assert np.array_equal(logits.cpu().numpy(), a)
+    assert np.array_equal(ranks.cpu().numpy(), orc.rank_experts(a, k + 1))
+    assert np.abs(probs.cpu().numpy() - orc.softmax_probs(a)).max() <= 1e-6
+
+
 # ------------------------------------------------------------------ capacity per group (Sec. 3 capacity read per GPU)
 QUOTA_CASES = [
     # T, E, G, k, cf, ties
