@@ -36,6 +36,28 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
+// Scheduling groups for the instruction scheduler (masks of sched_group_barrier: 0x008 MFMA,
+// 0x100 LDS read, 0x020 global or buffer load).  They order the instructions of the surrounding
+// scheduling region only; what the instructions compute is untouched.
+// N times "one MFMA, then one LDS read":
+template <int N>
+__device__ __forceinline__ void sched_mfma_lds_read() {
+  if constexpr (N > 0) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+    sched_mfma_lds_read<N - 1>();
+  }
+}
+// N times "one MFMA, then up to PER global loads":
+template <int N, int PER>
+__device__ __forceinline__ void sched_mfma_global_load() {
+  if constexpr (N > 0) {
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x020, PER, 0);
+    sched_mfma_global_load<N - 1, PER>();
+  }
+}
+
 __device__ inline u32 f32_to_bf16_bits(float f) {
   u32 u = __builtin_bit_cast(u32, f);
   u += 0x7fffu + ((u >> 16) & 1u);
@@ -425,15 +447,17 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
               acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[slot][j], af[slot][i], acc[i][j], 0, 0, 0);
           }
       };
-      // Software pipeline.  sched_barrier(0) pins the order "fragment loads of the NEXT k-step,
-      // then the MFMAs of the current one", so every LDS read has a whole MFMA block to complete
-      // in.  The last k-step of a chunk runs after the barrier, in whose shadow the global loads
-      // are issued.  The loop is rotated so that its body starts at the barrier (the compiler's
-      // wait counting is exact only inside one basic block).
+      // Software pipeline: the fragment loads of the NEXT k-step are spread over the MFMAs of the
+      // current one, one LDS read behind each of the first MFMAs.  (With all the reads in front
+      // of the MFMAs the LDS pipe is asked for 6 KB per wave in one burst and is then idle for the
+      // rest of the step; both waves of a SIMD doing so in turn leaves MFMA slots empty.)  The
+      // last k-step of a chunk runs after the barrier; the global loads of the stream go behind
+      // its last two MFMAs.  The loop is rotated so that its body starts at the barrier (the
+      // compiler's wait counting is exact only inside one basic block).
       auto step = [&](const char *sta, const char *stb, int ks_next, int slot_next, int slot_now) {
         load_frags(sta, stb, ks_next, slot_next);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_step(slot_now);
+        sched_mfma_lds_read<WM + WN>();
         __builtin_amdgcn_sched_barrier(0);
       };
       const char *sta = smem + sa * PK_A_STAGE, *stb = smem + PK_B_BASE + sb * PK_B_STAGE;
@@ -458,8 +482,9 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
         sta = smem + sa * PK_A_STAGE;
         stb = smem + PK_B_BASE + sb * PK_B_STAGE;
         load_frags(sta, stb, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
         mfma_step(1);  // last k-step of chunk kt-1
+        sched_mfma_lds_read<WM + WN>();
+        sched_mfma_global_load<2, 8>();
         // the stream's next loads: the rest of this tile, then the first two chunks of the next one
         if (kt + 2 < KT) {
           issue_a(cur, kt + 1, sa ^ 1);

@@ -30,7 +30,6 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int RT_THREADS = 256;
 constexpr int RT_NW = RT_THREADS / kWave;
-constexpr int RT_TS = kMaxE + 1;  // LDS row stride of a [token][expert] tile
 
 union Frag {
   u32 w[4];
