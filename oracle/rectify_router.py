@@ -25,6 +25,8 @@ Each function follows one passage of the paper, in the paper's order:
   combine_weights()     Eq. 2 and Eq. 3
   expert_ffn()          Sec. 5.1 "Model": experts are LLaMA FFNs (SwiGLU)
   moe_output()          Eq. 2 / Eq. 3 applied to expert outputs
+  router_score_gradient()  App. A (Eq. 5, Eq. 6): gradient of a loss with respect to
+                        the router scores through the Eq. 2 / Eq. 3 weights
 
 Readings taken where the paper is silent (each one is also a flag or a
 documented rule of the HIP library):
@@ -50,11 +52,22 @@ documented rule of the HIP library):
     slots [g Cq, (g+1) Cq) of that expert's queue of G Cq slots, and only the
     group's own tokens compete for them, in the top-k rounds and in Fill-in.
 
+  * App. A, Eq. 6 (printed garbled): the weight of a processed assignment is
+    n g_ij / S_i with g the softmax over ALL experts (Eq. 5), n its
+    multiplicity (1, or k - |R_i| for the Intra-GPU expert) and
+    S_i = sum over the token's processed assignments of n g_ij; the forward
+    value is that of Eq. 2 / Eq. 3.  In the backward pass S_i is a constant.
+    The routing decisions themselves (which experts, which tokens are kept)
+    carry no gradient.
+
 Parity pins (tests/test_oracle_*.py): a hand-worked capacity-3 example
 (tests/golden/), brute-force subset enumeration on tiny inputs, the
 "top-(k+1) router at unchanged capacity" formulation of Fill-in, the G=1
 special case of Intra-GPU Rectification, counting identities, the
-no-drop dense-mixture closed form, and the identical-experts closed form.
+no-drop dense-mixture closed form, and the identical-experts closed form;
+for router_score_gradient() central differences of the loss it differentiates,
+automatic differentiation of the same expressions, the dense-mixture softmax
+gradient and the single-expert cases App. A describes.
 The choice between the alternative readings listed above is "parity unpinned":
 the paper prints no number that discriminates them.
 """
@@ -370,3 +383,64 @@ def moe_forward(x, w_router, bias, w1, w3, w2, k, G, capacity_factor, act,
     tables = route(a, k, G, capacity_factor, intra_gpu, fill_in, policy, quota)
     out = moe_output(x, tables, k, w1, w3, w2, act, tokens)
     return a, tables, out
+
+
+# ----------------------------------------------------------------------------
+# App. A: gradient of a loss L with respect to the router scores a_ij, through
+# the weights of Eq. 2 / Eq. 3 only (routing decisions are piecewise constant).
+# The processed assignments of token i are p = (expert e_p, multiplicity n_p):
+# kept top-k ranks and a placed fill-in with n = 1, the Intra-GPU expert with
+# n = k - |R_i| (Eq. 3).  Eq. 2 / Eq. 3: o_i = sum_p c_ip E_{e_p}(x_i), so
+#   dL/dc_ip = <dL/do_i, E_{e_p}(x_i)>.
+# ----------------------------------------------------------------------------
+def processed_assignments(tables, k, i):
+    """[(column of combine_w, expert, multiplicity)] of token i."""
+    out = []
+    for r in range(k + 1):
+        if tables["slot"][i, r] >= 0:
+            out.append((r, int(tables["rank_expert"][i, r]), 1.0))
+    if tables["ir_expert"][i] >= 0:
+        out.append((k + 1, int(tables["ir_expert"][i]), float(tables["n_drop"][i])))
+    return out
+
+
+def router_score_gradient(x, a, tables, k, w1, w3, w2, act, dout, straight_through=True, tokens=None):
+    """Returns (dL/dc [n, k+2], dL/da [n, E]) for `tokens` (default: all), float64.
+
+    straight_through=True: App. A, Eq. 6.  c_ip = n_p g_{i,e_p} / S_i with g the softmax over all
+    experts (Eq. 5); S_i is held constant, so dL/dg_ij = sum_{p: e_p = j} n_p dL/dc_ip / S_i, and
+    dL/da_il = sum_j dL/dg_ij dg_ij/da_il with the softmax Jacobian dg_ij/da_il = g_ij ([j = l] - g_il).
+    straight_through=False: the plain derivative of the normalised weights
+    c_ip = n_p exp(a_{i,e_p}) / Z_i, Z_i = sum_q n_q exp(a_{i,e_q}) (quotient rule)."""
+    x = np.asarray(x)
+    a64 = np.asarray(a, dtype=np.float32).astype(np.float64)
+    T, E = a64.shape
+    tokens = np.arange(T) if tokens is None else np.asarray(tokens)
+    dout = np.asarray(dout, dtype=np.float64)
+    g = softmax_probs(a64)
+    dc = np.zeros((len(tokens), k + 2), dtype=np.float64)
+    da = np.zeros((len(tokens), E), dtype=np.float64)
+    for n, i in enumerate(tokens):
+        P = processed_assignments(tables, k, i)
+        if not P:
+            continue
+        for col, e, mult in P:
+            y = expert_ffn(x[i:i + 1], w1[e], None if w3 is None else w3[e], w2[e], act)[0]
+            dc[n, col] = float(dout[i] @ y)
+        if straight_through:
+            S = sum(mult * g[i, e] for _, e, mult in P)
+            dg = np.zeros(E, dtype=np.float64)
+            for col, e, mult in P:
+                dg[e] += mult * dc[n, col] / S
+            jac = np.diag(g[i]) - np.outer(g[i], g[i])  # jac[j, l] = dg_ij / da_il
+            da[n] = dg @ jac
+        else:
+            t = np.array([mult * math.exp(a64[i, e] - a64[i].max()) for _, e, mult in P])
+            Z = t.sum()
+            c = t / Z
+            for p, (col, e, mult) in enumerate(P):
+                # dc_p/da_l = [e_p = l] c_p - c_p * sum_{q: e_q = l} c_q
+                da[n, e] += dc[n, col] * c[p]
+                for q, (_, eq, _) in enumerate(P):
+                    da[n, eq] -= dc[n, col] * c[p] * c[q]
+    return dc, da

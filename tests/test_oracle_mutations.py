@@ -327,6 +327,76 @@ def m_quota_fill_in_over_all_groups(mp):
     mp.setattr(orc, "fill_in_rectification_quota", fr)
 
 
+# ------------------------------------------------------------------ App. A gradient
+def _gradient_with(jacobian=None, normaliser_constant=True, multiplicity=lambda m: m, dc_sign=1.0, mass=None):
+    """router_score_gradient re-built with one piece exchangeable."""
+    def grad(x, a, tables, k, w1, w3, w2, act, dout, straight_through=True, tokens=None):
+        a64 = np.asarray(a, dtype=np.float32).astype(np.float64)
+        T, E = a64.shape
+        tokens = np.arange(T) if tokens is None else np.asarray(tokens)
+        g = np.exp(a64 - a64.max(axis=1, keepdims=True))
+        g /= g.sum(axis=1, keepdims=True)
+        dc = np.zeros((len(tokens), k + 2))
+        da = np.zeros((len(tokens), E))
+        for n, i in enumerate(tokens):
+            P = [(c, e, multiplicity(m)) for c, e, m in orc.processed_assignments(tables, k, i)]
+            if not P:
+                continue
+            for col, e, m in P:
+                y = orc.expert_ffn(x[i:i + 1], w1[e], None if w3 is None else w3[e], w2[e], act)[0]
+                dc[n, col] = dc_sign * float(np.asarray(dout, dtype=np.float64)[i] @ y)
+            t = np.array([m * g[i, e] for _, e, m in P])
+            c = t / t.sum()
+            D = float(sum(c[p] * dc[n, col] for p, (col, _, _) in enumerate(P)))
+            if straight_through and normaliser_constant:
+                dg = np.zeros(E)
+                for col, e, m in P:
+                    dg[e] += m * dc[n, col] / t.sum()
+                jac = jacobian(g[i]) if jacobian else np.diag(g[i]) - np.outer(g[i], g[i])
+                da[n] = dg @ jac
+            else:
+                for p, (col, e, m) in enumerate(P):
+                    da[n, e] += c[p] * dc[n, col]
+                w = np.zeros(E)
+                for p, (_, e, _) in enumerate(P):
+                    w[e] += c[p]
+                da[n] -= (mass(g[i], w) if mass else w) * D
+        return dc, da
+    return grad
+
+
+def m_gradient_normaliser_not_held_constant(mp):
+    mp.setattr(orc, "router_score_gradient", _gradient_with(normaliser_constant=False))
+
+
+def m_gradient_softmax_jacobian_sign(mp):
+    mp.setattr(orc, "router_score_gradient", _gradient_with(jacobian=lambda g: np.diag(g) + np.outer(g, g)))
+
+
+def m_gradient_softmax_jacobian_without_diagonal_scale(mp):
+    mp.setattr(orc, "router_score_gradient", _gradient_with(jacobian=lambda g: np.eye(len(g)) - np.outer(g, g)))
+
+
+def m_gradient_forgets_the_drop_count(mp):
+    mp.setattr(orc, "router_score_gradient", _gradient_with(multiplicity=lambda m: 1.0))
+
+
+def m_gradient_of_the_negated_loss(mp):
+    mp.setattr(orc, "router_score_gradient", _gradient_with(dc_sign=-1.0))
+
+
+def m_plain_gradient_subtracts_the_gate_probability(mp):
+    # the straight-through closed form used where the plain derivative is asked for
+    real = orc.router_score_gradient
+    mp.setattr(orc, "router_score_gradient",
+               lambda *a, straight_through=True, **kw: real(*a, straight_through=True, **kw))
+
+
+def m_gradient_ignores_the_fill_in_column(mp):
+    real = orc.processed_assignments
+    mp.setattr(orc, "processed_assignments", lambda t, k, i: [p for p in real(t, k, i) if p[0] != k])
+
+
 MUTATIONS = [
     m_keep_lowest_scores, m_token_tie_break_reversed, m_expert_tie_break_reversed, m_capacity_floor,
     m_slots_in_score_order, m_rounds_forget_earlier_fill, m_ir_tokens_interleaved_over_groups, m_ir_ignores_groups,
@@ -334,7 +404,10 @@ MUTATIONS = [
     m_ir_term_without_drop_count, m_weights_are_gate_probabilities, m_swiglu_gate_and_up_swapped,
     m_gelu_tanh_approximation, m_down_projection_read_in_the_wrong_layout, m_router_bias_subtracted, m_softmax_over_tokens,
     m_output_ignores_fill_in, m_output_ignores_intra_gpu, m_quota_ignores_groups, m_quota_capacity_from_all_tokens,
-    m_quota_fill_in_over_all_groups,
+    m_quota_fill_in_over_all_groups, m_gradient_normaliser_not_held_constant, m_gradient_softmax_jacobian_sign,
+    m_gradient_softmax_jacobian_without_diagonal_scale, m_gradient_forgets_the_drop_count,
+    m_gradient_of_the_negated_loss, m_plain_gradient_subtracts_the_gate_probability,
+    m_gradient_ignores_the_fill_in_column,
 ]
 
 

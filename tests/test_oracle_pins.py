@@ -719,3 +719,190 @@ def test_more_capacity_never_drops_more(seed):
             assert prev <= kept
         prev = kept
     assert len(prev) == T * k  # capacity factor E: every queue holds all T tokens
+
+
+# ---------------------------------------------------------------- App. A: gradient of the router scores
+def _grad_case(seed, T=32, E=8, k=2, G=2, cf=1.0, d=12, F=20, ir=True, fr=True, act="swiglu", grid=None):
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, d))
+    wr = rng.standard_normal((E, d)) * 0.4
+    w1 = rng.standard_normal((E, F, d)) * 0.3
+    w3 = rng.standard_normal((E, F, d)) * 0.3 if act == "swiglu" else None
+    w2 = rng.standard_normal((E, d, F)) * 0.3
+    a = orc.router_scores(x, wr)
+    if grid is not None:  # scores on a grid that float32 steps of `grid` stay on
+        a = (np.round(a.astype(np.float64) / grid) * grid).astype(np.float32)
+    t = orc.route(a, k, G, cf, intra_gpu=ir, fill_in=fr)
+    dout = rng.standard_normal((T, d))
+    return dict(x=x, a=a, t=t, k=k, w=(w1, w3, w2), act=act, dout=dout, T=T, E=E)
+
+
+def _assignments(t, k, i):
+    """(combine_w column, expert, multiplicity) of token i, read off the tables by hand."""
+    P = [(r, int(t["rank_expert"][i, r]), 1.0) for r in range(k + 1) if t["slot"][i, r] >= 0]
+    if t["ir_expert"][i] >= 0:
+        P.append((k + 1, int(t["ir_expert"][i]), float(k - sum(t["slot"][i, r] >= 0 for r in range(k)))))
+    return P
+
+
+def _expert_out(c, i, e):
+    w1, w3, w2 = c["w"]
+    return orc.expert_ffn(c["x"][i:i + 1], w1[e], None if w3 is None else w3[e], w2[e], c["act"])[0]
+
+
+GRAD_CASES = [dict(seed=1), dict(seed=2, k=1, cf=1.25), dict(seed=3, k=2, cf=0.5, ir=True, fr=False),
+              dict(seed=4, k=2, cf=2.5, ir=False, fr=True), dict(seed=4, k=1, cf=1.25, ir=False, fr=True), dict(seed=5, k=3, E=8, G=4, cf=1.5, act="gelu"),
+              dict(seed=6, k=2, cf=0.75, ir=False, fr=False)]
+
+
+@pytest.mark.parametrize("case", GRAD_CASES)
+@pytest.mark.parametrize("st", [True, False])
+def test_gradient_matches_central_differences_of_the_weights(case, st):
+    """dL/da against (L(a + h e_l) - L(a - h e_l)) / 2h, L = sum_p dL/dc_p c_p(a), with the
+    normaliser frozen at its unperturbed value for the straight-through form (App. A, Eq. 6)."""
+    c = _grad_case(**case)
+    k, t = c["k"], c["t"]
+    dc, da = orc.router_score_gradient(c["x"], c["a"], t, k, *c["w"], c["act"], c["dout"], straight_through=st)
+    h = 1e-6
+    for i in range(c["T"]):
+        P = _assignments(t, k, i)
+        a0 = c["a"][i].astype(np.float64)
+
+        def softmax(v):
+            z = np.exp(v - v.max())
+            return z / z.sum()
+        S0 = sum(m * softmax(a0)[e] for _, e, m in P)
+
+        def loss(v):
+            if st:
+                return sum(dc[i, col] * m * softmax(v)[e] / S0 for col, e, m in P)
+            Z = sum(m * math.exp(v[e]) for _, e, m in P)
+            return sum(dc[i, col] * m * math.exp(v[e]) / Z for col, e, m in P)
+        for l in range(c["E"]):
+            up, dn = a0.copy(), a0.copy()
+            up[l] += h
+            dn[l] -= h
+            fd = (loss(up) - loss(dn)) / (2 * h)
+            assert abs(fd - da[i, l]) <= 1e-7 * (1.0 + abs(fd)), (i, l, fd, da[i, l])
+
+
+@pytest.mark.parametrize("case", GRAD_CASES)
+def test_plain_gradient_matches_differences_of_the_forward_output(case):
+    """Without the straight-through trick the gradient is that of the layer as the forward
+    computes it: L(a) = <dL/do, o(a)> with o from moe_output and the weights from
+    combine_weights at perturbed scores (decisions frozen)."""
+    grid = 2.0 ** -9
+    c = _grad_case(**case, grid=grid)
+    k, t = c["k"], c["t"]
+    _, da = orc.router_score_gradient(c["x"], c["a"], t, k, *c["w"], c["act"], c["dout"], straight_through=False)
+
+    def loss(a):
+        tt = dict(t)
+        tt["combine_w"] = orc.combine_weights(a, t["rank_expert"], t["slot"], k, t["n_drop"], t["ir_expert"])
+        return (orc.moe_output(c["x"], tt, k, *c["w"], c["act"]) * c["dout"]).sum(axis=1)  # per token
+
+    h = 8 * grid
+    for l in range(c["E"]):
+        up, dn = c["a"].copy(), c["a"].copy()
+        up[:, l] += np.float32(h)
+        dn[:, l] -= np.float32(h)
+        fd = (loss(up) - loss(dn)) / (2 * h)
+        assert np.allclose(fd, da[:, l], rtol=2e-3, atol=2e-4 * np.abs(da).max()), l
+
+
+@pytest.mark.parametrize("case", GRAD_CASES)
+@pytest.mark.parametrize("st", [True, False])
+def test_gradient_matches_automatic_differentiation(case, st):
+    torch = pytest.importorskip("torch")
+    c = _grad_case(**case)
+    k, t = c["k"], c["t"]
+    dc, da = orc.router_score_gradient(c["x"], c["a"], t, k, *c["w"], c["act"], c["dout"], straight_through=st)
+    a = torch.tensor(c["a"].astype(np.float64), requires_grad=True)
+    g = torch.softmax(a, dim=1)
+    loss = torch.zeros((), dtype=torch.float64)
+    for i in range(c["T"]):
+        P = _assignments(t, k, i)
+        if not P:
+            continue
+        terms = torch.stack([m * g[i, e] for _, e, m in P])
+        S = terms.sum()
+        weights = terms / (S.detach() if st else S)
+        loss = loss + (weights * torch.tensor([dc[i, col] for col, _, _ in P], dtype=torch.float64)).sum()
+    loss.backward()
+    assert np.allclose(a.grad.numpy(), da, rtol=1e-9, atol=1e-12)
+
+
+def test_weight_gradient_is_the_projection_of_the_expert_output():
+    """Eq. 2 / Eq. 3 are linear in the weights: sum_p c_p dL/dc_p = <dL/do_i, o_i>, and each
+    dL/dc_p is <dL/do_i, E_j(x_i)> in the combine_w column of that assignment."""
+    for case in GRAD_CASES:
+        c = _grad_case(**case)
+        k, t = c["k"], c["t"]
+        dc, _ = orc.router_score_gradient(c["x"], c["a"], t, k, *c["w"], c["act"], c["dout"])
+        o = orc.moe_output(c["x"], t, k, *c["w"], c["act"])
+        assert np.allclose((t["combine_w"] * dc).sum(axis=1), (o * c["dout"]).sum(axis=1), rtol=1e-10, atol=1e-12)
+        for i in range(c["T"]):
+            used = {col: e for col, e, _ in _assignments(t, k, i)}
+            for col in range(k + 2):
+                want = float(c["dout"][i] @ _expert_out(c, i, used[col])) if col in used else 0.0
+                assert abs(dc[i, col] - want) <= 1e-12 * (1 + abs(want))
+
+
+def test_dense_mixture_gradient_is_the_softmax_gradient():
+    """k = E and room for everybody: the weights are the softmax itself, S_i = 1, and both forms
+    give dL/da_l = g_l (v_l - sum_j g_j v_j) with v_j = <dL/do_i, E_j(x_i)>."""
+    c = _grad_case(seed=11, E=4, k=4, G=2, cf=4.0, ir=True, fr=False)
+    k, t = c["k"], c["t"]
+    assert (t["slot"][:, :k] >= 0).all()
+    g = np.exp(c["a"].astype(np.float64))
+    g /= g.sum(axis=1, keepdims=True)
+    v = np.array([[c["dout"][i] @ _expert_out(c, i, e) for e in range(c["E"])] for i in range(c["T"])])
+    want = g * (v - (g * v).sum(axis=1, keepdims=True))
+    for st in (True, False):
+        _, da = orc.router_score_gradient(c["x"], c["a"], t, k, *c["w"], c["act"], c["dout"], straight_through=st)
+        assert np.allclose(da, want, rtol=1e-10, atol=1e-13)
+
+
+def test_single_available_expert_has_a_gradient_only_with_the_straight_through_form():
+    """App. A, second issue: top-2, first routing kept, second dropped -> normalising over the one
+    available expert gives the constant 1 and a zero gradient; with the normaliser held constant
+    the gradient is v ([l = e] - g_l), v = <dL/do_i, E_e(x_i)>."""
+    c = _grad_case(seed=12, T=48, k=2, cf=0.5, ir=False, fr=False)
+    k, t = c["k"], c["t"]
+    single = np.flatnonzero((t["slot"][:, 0] >= 0) & (t["slot"][:, 1] < 0))
+    assert len(single) >= 5
+    dc, da_st = orc.router_score_gradient(c["x"], c["a"], t, k, *c["w"], c["act"], c["dout"], straight_through=True)
+    _, da_plain = orc.router_score_gradient(c["x"], c["a"], t, k, *c["w"], c["act"], c["dout"], straight_through=False)
+    g = np.exp(c["a"].astype(np.float64))
+    g /= g.sum(axis=1, keepdims=True)
+    for i in single:
+        e = t["rank_expert"][i, 0]
+        assert np.abs(da_plain[i]).max() <= 1e-15 * abs(dc[i, 0])
+        want = dc[i, 0] * ((np.arange(c["E"]) == e) - g[i])
+        assert np.allclose(da_st[i], want, rtol=1e-12, atol=1e-15)
+        assert np.abs(da_st[i]).max() > 0
+
+
+@pytest.mark.parametrize("case", GRAD_CASES)
+def test_inactive_experts_feel_the_gradient_only_with_the_straight_through_form(case):
+    """App. A, first issue: normalised over the processed set, a score outside it gets no
+    gradient; through the softmax over all experts it gets -g_l <dL/do_i, o_i>.  Both forms are
+    invariant to a shift of a token's scores (rows sum to zero), and a token that no expert
+    processes has no gradient."""
+    c = _grad_case(**case)
+    k, t = c["k"], c["t"]
+    dc, da_st = orc.router_score_gradient(c["x"], c["a"], t, k, *c["w"], c["act"], c["dout"], straight_through=True)
+    _, da_plain = orc.router_score_gradient(c["x"], c["a"], t, k, *c["w"], c["act"], c["dout"], straight_through=False)
+    o = orc.moe_output(c["x"], t, k, *c["w"], c["act"])
+    g = np.exp(c["a"].astype(np.float64))
+    g /= g.sum(axis=1, keepdims=True)
+    for i in range(c["T"]):
+        inside = {e for _, e, _ in _assignments(t, k, i)}
+        outside = [l for l in range(c["E"]) if l not in inside]
+        if not inside:
+            assert not da_st[i].any() and not da_plain[i].any()
+            continue
+        assert not da_plain[i, outside].any()
+        assert np.allclose(da_st[i, outside], -g[i, outside] * (c["dout"][i] @ o[i]), rtol=1e-10, atol=1e-14)
+        assert abs(da_st[i].sum()) <= 1e-12 * np.abs(dc[i]).max()
+        assert abs(da_plain[i].sum()) <= 1e-12 * np.abs(dc[i]).max()
