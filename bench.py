@@ -123,6 +123,21 @@ def run_forward(rr, wl, torch, w, mode, steps, warmup, quota=False):
     rr.rr_profile_enable(False)
     kernels = {n: ms / max(c, 1) for n, (c, ms) in prof.items() if c > 0}
 
+    # App. A backward of the weights (not part of the step): gradient of the router scores from the
+    # forward pass's expert outputs, straight-through form
+    dout = wl.make_output_gradient_device(w)
+    dlogits = torch.empty((w.T, w.E), dtype=torch.float32, device="cuda")
+    dcw = torch.empty((w.T, w.k + 2), dtype=torch.float32, device="cuda")
+    for _ in range(warmup):
+        rr.rr_router_backward(cfg, dout, logits, tables, ws, dlogits, dcw, True)
+    rr.rr_profile_enable(True)
+    for _ in range(steps):
+        rr.rr_router_backward(cfg, dout, logits, tables, ws, dlogits, dcw, True)
+    bwd_ms = rr.rr_profile_read()["router_backward"]
+    bwd_ms = bwd_ms[1] / max(bwd_ms[0], 1)
+    rr.rr_profile_enable(False)
+    del dout
+
     th = tables.to_host()
     C = tables.capacity
     slot_rows = int(th["fill_total"].sum())
@@ -157,6 +172,9 @@ def run_forward(rr, wl, torch, w, mode, steps, warmup, quota=False):
     roofline["avg_ms"] = kernels[dom]
     if dom in flops:
         roofline["flops_per_launch"] = flops[dom]
+    # backward: dL/do and the rows of y once, logits and weights in, both gradients out, the token's table entries
+    bwd_bytes = (n_src + T) * d * es + 2 * T * E * 4 + 2 * T * (k + 2) * 4 + T * (k + 1) * 8 + 8 * T
+    bwd_gbs = bwd_bytes / (bwd_ms * 1e-3) / 1e9
     ffn_ms = kernels.get("ffn_gate_up", 0) + kernels.get("ffn_down", 0)
     routing_names = ("router_scores", "topk_rank", "scan_candidates", "scatter_candidates",
                      "select_slot", "ir_count", "ir_scan", "ir_weights")
@@ -169,6 +187,8 @@ def run_forward(rr, wl, torch, w, mode, steps, warmup, quota=False):
                             for n, v in per_kernel.items()},
         "ffn_tflops": (flops["ffn_gate_up"] + flops["ffn_down"]) / (ffn_ms * 1e-3) / 1e12 if ffn_ms else None,
         "routing_rectify_mtokens_per_s": T / (routing_ms * 1e-3) / 1e6 if routing_ms else None,
+        "router_backward": {"ms": round(bwd_ms, 5), "bound": "hbm", "achieved": round(bwd_gbs, 1), "unit": "GB/s",
+                            "frac": round(bwd_gbs / PEAK_HBM_GBS, 4), "bytes_per_launch": bwd_bytes},
         "rows": {"slot_rows": slot_rows, "ir_rows": ir_rows, "capacity_slots": E * C,
                  "dropped_assignments": int((th["slot"][:, :k] < 0).sum()),
                  "fill_in_placed": int((th["slot"][:, k] >= 0).sum()), "padding_slots": E * C - slot_rows},
@@ -304,7 +324,8 @@ def main():
         torch.cuda.empty_cache()
         paper_shape = {"workload": wl.C3.name, "mode": "top2+ir+fr", "ms_per_step": r3["ms_per_step"],
                        "tokens_per_s": r3["tokens_per_s"], "ffn_tflops": r3["ffn_tflops"],
-                       "kernel_ms": r3["kernel_ms"], "kernel_roofline": r3["kernel_roofline"], "rows": r3["rows"]}
+                       "kernel_ms": r3["kernel_ms"], "kernel_roofline": r3["kernel_roofline"], "rows": r3["rows"],
+                       "router_backward": r3["router_backward"]}
     stress = None if (args.no_routing_stress or args.no_extras) else routing_stress(rr, wl, torch, args.steps, args.warmup,
                                                                                     cpu=args.cpu_sample > 0)
     if args.copy_probe:
@@ -332,6 +353,7 @@ def main():
         "ffn_tflops": res["ffn_tflops"],
         "routing_rectify_mtokens_per_s": res["routing_rectify_mtokens_per_s"],
         "rows": res["rows"],
+        "router_backward": res["router_backward"],
         "paper_shape": paper_shape,
         "routing_stress": stress,
     }

@@ -140,6 +140,28 @@ int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, c
                    const rr_tables *tables, float *logits,
                    void *workspace, size_t workspace_bytes, void *stream);
 
+/* App. A: gradient of a loss L with respect to the router scores through the weights of Eq. 2 /
+ * Eq. 3, after an rr_moe_forward call with the same cfg (d_ff > 0) and the same workspace, which
+ * must not have been written since: the expert outputs E_j(x_i) and the row layout are read from it.
+ * The routing decisions carry no gradient.
+ *   dout       [T,d_model] cfg->dtype: dL/d out
+ *   logits     the forward call's logits [T,E] fp32; NULL if that call was given none
+ *   tables     the forward call's tables; NULL if that call was given none
+ *   grad_flags RR_GRAD_STRAIGHT_THROUGH: App. A, Eq. 6 - the weights are n g_ij / S_i with g the
+ *              softmax over all experts (Eq. 5), and their normaliser S_i is a constant in the
+ *              backward pass, so that a token with a single available expert still has a gradient:
+ *                dL/da_il = sum_{p -> expert l} c_ip dL/dc_ip - g_il sum_p c_ip dL/dc_ip.
+ *              0: the plain derivative of the normalised weights (g_il replaced by the weight
+ *              mass of expert l; zero for a token with a single available expert).
+ *   dcombine_w [T,k+2] fp32 out or NULL: dL/dc_ip = <dL/do_i, E_j(x_i)> in the columns of
+ *              rr_tables.combine_w, 0 where the token has no such assignment
+ *   dlogits    [T,E] fp32 out: dL/da_ij; a row of zeros for a token that no expert processed
+ * Dot products and the softmax are accumulated in fp32. */
+#define RR_GRAD_STRAIGHT_THROUGH 1u
+int rr_router_backward(const rr_config *cfg, const void *dout, const float *logits,
+                       const rr_tables *tables, void *workspace, size_t workspace_bytes,
+                       uint32_t grad_flags, float *dcombine_w, float *dlogits, void *stream);
+
 /* Per-kernel timing for benchmarks.  While enabled, every kernel the library launches is bracketed
  * by HIP events on the call's stream (events are created on first use and kept).  rr_profile_read
  * synchronises the device, adds up the time of every recorded launch per kernel and clears the

@@ -416,17 +416,24 @@ def router_score_gradient(x, a, tables, k, w1, w3, w2, act, dout, straight_throu
     a64 = np.asarray(a, dtype=np.float32).astype(np.float64)
     T, E = a64.shape
     tokens = np.arange(T) if tokens is None else np.asarray(tokens)
-    dout = np.asarray(dout, dtype=np.float64)
     g = softmax_probs(a64)
     dc = np.zeros((len(tokens), k + 2), dtype=np.float64)
     da = np.zeros((len(tokens), E), dtype=np.float64)
+    assigned = [processed_assignments(tables, k, i) for i in tokens]
+    # dL/dc_ip = <dL/do_i, E_j(x_i)>, one expert at a time over the tokens it processes
+    for j in range(E):
+        users = [(n, col) for n, P in enumerate(assigned) for col, e, _ in P if e == j]
+        if not users:
+            continue
+        rows = np.array(sorted({n for n, _ in users}))
+        y = expert_ffn(x[tokens[rows]], w1[j], None if w3 is None else w3[j], w2[j], act)
+        proj = dict(zip(rows.tolist(), (y * np.asarray(dout[tokens[rows]], dtype=np.float64)).sum(axis=1)))
+        for n, col in users:
+            dc[n, col] = proj[n]
     for n, i in enumerate(tokens):
-        P = processed_assignments(tables, k, i)
+        P = assigned[n]
         if not P:
             continue
-        for col, e, mult in P:
-            y = expert_ffn(x[i:i + 1], w1[e], None if w3 is None else w3[e], w2[e], act)[0]
-            dc[n, col] = float(dout[i] @ y)
         if straight_through:
             S = sum(mult * g[i, e] for _, e, mult in P)
             dg = np.zeros(E, dtype=np.float64)

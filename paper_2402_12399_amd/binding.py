@@ -12,6 +12,7 @@ from dataclasses import dataclass
 RR_F32, RR_BF16 = 0, 1
 RR_ACT_GELU, RR_ACT_SWIGLU = 0, 1
 RR_INTRA_GPU, RR_FILL_IN, RR_POLICY_ARRIVAL, RR_QUOTA_PER_GROUP = 1, 2, 4, 8
+RR_GRAD_STRAIGHT_THROUGH = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -83,6 +84,8 @@ def load_library():
     lib.rr_rectified_dispatch.argtypes = [C.POINTER(_Config), vp, C.POINTER(_Tables), vp, sz, vp]
     lib.rr_moe_forward.restype = C.c_int
     lib.rr_moe_forward.argtypes = [C.POINTER(_Config), vp, vp, vp, vp, vp, vp, vp, C.POINTER(_Tables), vp, vp, sz, vp]
+    lib.rr_router_backward.restype = C.c_int
+    lib.rr_router_backward.argtypes = [C.POINTER(_Config), vp, vp, C.POINTER(_Tables), vp, sz, C.c_uint32, vp, vp, vp]
     lib.rr_profile_enable.restype = C.c_int
     lib.rr_profile_enable.argtypes = [C.c_int]
     lib.rr_profile_read.restype = C.c_int
@@ -186,6 +189,16 @@ def rr_moe_forward(cfg: RRConfig, x, w_router, bias, w1, w3, w2, out, tables: Ta
                                          _ptr(w2), _ptr(out), C.byref(tc) if tc is not None else None,
                                          _ptr(logits), _ptr(workspace), workspace.numel(), _stream()),
            "rr_moe_forward")
+
+
+def rr_router_backward(cfg: RRConfig, dout, logits, tables: Tables | None, workspace, dlogits, dcombine_w=None,
+                       straight_through: bool = True):
+    cc = cfg.c()
+    tc = tables.c() if tables is not None else None
+    _check(load_library().rr_router_backward(C.byref(cc), _ptr(dout), _ptr(logits),
+                                             C.byref(tc) if tc is not None else None, _ptr(workspace),
+                                             workspace.numel(), RR_GRAD_STRAIGHT_THROUGH if straight_through else 0,
+                                             _ptr(dcombine_w), _ptr(dlogits), _stream()), "rr_router_backward")
 
 
 def rr_profile_enable(on: bool):

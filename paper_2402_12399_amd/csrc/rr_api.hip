@@ -16,7 +16,8 @@ static std::vector<hipEvent_t> g_free_events;
 static hipEvent_t g_open[K_COUNT];
 static const char *const g_kernel_names[K_COUNT] = {
     "router_scores", "topk_rank", "scan_candidates", "scatter_candidates", "select_slot",
-    "ir_count", "ir_scan", "ir_weights", "dispatch_gather", "ffn_gate_up", "ffn_down", "combine"};
+    "ir_count", "ir_scan", "ir_weights", "dispatch_gather", "ffn_gate_up", "ffn_down", "combine",
+    "router_backward"};
 
 static hipEvent_t get_event() {
   if (!g_free_events.empty()) {
@@ -243,6 +244,27 @@ int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, c
   if (e == hipSuccess && !ffn_fuses_gather(D)) e = launch_gather(D, x, tb, W, s);
   if (e == hipSuccess) e = launch_ffn(D, x, tb, w1, w3, w2, W, s);
   if (e == hipSuccess) e = launch_combine(D, tb, W, out, s);
+  return e == hipSuccess ? RR_OK : RR_ERR_HIP;
+}
+
+int rr_router_backward(const rr_config *cfg, const void *dout, const float *logits, const rr_tables *tables,
+                       void *workspace, size_t workspace_bytes, uint32_t grad_flags, float *dcombine_w,
+                       float *dlogits, void *stream) {
+  if (!cfg) return RR_ERR_INVALID_ARG;
+  Dims D;
+  int rc = make_dims(cfg, true, &D);  // the expert outputs of a full forward call are needed
+  if (rc != RR_OK) return rc;
+  if (!dout || !dlogits) return RR_ERR_INVALID_ARG;
+  if (grad_flags & ~(uint32_t)RR_GRAD_STRAIGHT_THROUGH) return RR_ERR_INVALID_ARG;
+  if (tables && !tables_complete(tables)) return RR_ERR_INVALID_ARG;
+  Work W;
+  memset(&W, 0, sizeof(W));
+  rc = check_ws(D, true, workspace, workspace_bytes, &W);
+  if (rc != RR_OK) return rc;
+  const rr_tables &tb = tables ? *tables : W.tables;
+  const float *lg = logits ? logits : W.logits;
+  hipError_t e = launch_router_backward(D, dout, lg, tb, W, (grad_flags & RR_GRAD_STRAIGHT_THROUGH) != 0, dcombine_w,
+                                        dlogits, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
 }
 

@@ -78,7 +78,7 @@ struct Launch {
 // Kernel ids for the profiling record.
 enum KernelId {
   K_ROUTER = 0, K_TOPK, K_SCAN_CAND, K_SCATTER_CAND, K_SELECT_SLOT,
-  K_IR_COUNT, K_IR_SCAN, K_IR_WEIGHTS, K_GATHER, K_FFN_UP, K_FFN_DOWN, K_COMBINE,
+  K_IR_COUNT, K_IR_SCAN, K_IR_WEIGHTS, K_GATHER, K_FFN_UP, K_FFN_DOWN, K_COMBINE, K_ROUTER_BWD,
   K_COUNT
 };
 
@@ -111,5 +111,9 @@ bool ffn_fuses_gather(const Dims &D);  // the up projection reads x through the 
 hipError_t launch_ffn(const Dims &D, const void *x, const rr_tables &tb, const void *w1, const void *w3,
                       const void *w2, const Work &W, hipStream_t s);
 hipError_t launch_combine(const Dims &D, const rr_tables &tb, const Work &W, void *out, hipStream_t s);
+// reads the expert outputs, row bases and block offsets that the forward pass left in W
+hipError_t launch_router_backward(const Dims &D, const void *dout, const float *logits, const rr_tables &tb,
+                                  const Work &W, bool straight_through, float *dcombine_w, float *dlogits,
+                                  hipStream_t s);
 
 }  // namespace rr

@@ -131,6 +131,20 @@ def make_inputs_device(w: Workload, device="cuda", with_experts: bool = True):
     return out
 
 
+def make_output_gradient(w: Workload, T: int | None = None) -> np.ndarray:
+    """dL/d out for the backward pass of a workload: N(0,1) in storage form, from its own seed."""
+    rng = np.random.default_rng(w.seed + 7919)
+    return _store(rng.standard_normal((w.T if T is None else T, w.d_model), dtype=np.float32), w.dtype)
+
+
+def make_output_gradient_device(w: Workload, device="cuda"):
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(w.seed + 7919)
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    return torch.randn((w.T, w.d_model), generator=gen, device=device, dtype=torch.float32).to(tdt)
+
+
 def synthetic_logits(T: int, E: int, seed: int, bias_std: float = 1.0, ties: bool = False) -> np.ndarray:
     """fp32 router logits drawn directly (for routing-table parity with identical logits).
 

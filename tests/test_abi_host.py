@@ -27,7 +27,7 @@ def test_every_declared_function_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "rr.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(rr_[a-z_]+)\s*\(", header))
-    assert {"rr_capacity", "rr_slots_per_expert", "rr_workspace_bytes", "rr_router_scores", "rr_rectified_dispatch", "rr_moe_forward",
+    assert {"rr_capacity", "rr_slots_per_expert", "rr_workspace_bytes", "rr_router_scores", "rr_rectified_dispatch", "rr_moe_forward", "rr_router_backward",
             "rr_profile_enable", "rr_profile_read", "rr_strerror"} <= declared
     for name in declared:
         assert hasattr(lib, name), f"{name} declared in rr.h but not exported by librr.so"
@@ -140,6 +140,14 @@ def test_entry_points_reject_bad_arguments_on_the_host(lib):
     assert lib.rr_moe_forward(C.byref(bad), fake, fake, None, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == INVALID
     nofnn = _cfg(d_ff=0).c()
     assert lib.rr_moe_forward(C.byref(nofnn), fake, fake, None, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == INVALID
+    # backward: missing gradient buffers, unknown flag, incomplete tables, no expert outputs to read, workspace
+    assert lib.rr_router_backward(C.byref(cc), None, fake, None, fake, 1 << 40, 1, None, fake, None) == INVALID
+    assert lib.rr_router_backward(C.byref(cc), fake, fake, None, fake, 1 << 40, 1, None, None, None) == INVALID
+    assert lib.rr_router_backward(C.byref(cc), fake, fake, None, fake, 1 << 40, 2, None, fake, None) == INVALID
+    assert lib.rr_router_backward(C.byref(cc), fake, fake, C.byref(holes), fake, 1 << 40, 1, None, fake, None) == INVALID
+    assert lib.rr_router_backward(C.byref(nofnn), fake, fake, None, fake, 1 << 40, 1, None, fake, None) == INVALID
+    assert lib.rr_router_backward(C.byref(cc), fake, fake, None, fake, 256, 1, None, fake, None) == WORKSPACE
+    assert lib.rr_router_backward(C.byref(cc), fake, fake, None, None, 1 << 40, 1, None, fake, None) == WORKSPACE
 
 
 def test_missing_library_fails_loudly(monkeypatch):
