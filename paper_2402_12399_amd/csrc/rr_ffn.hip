@@ -79,7 +79,7 @@ __device__ inline float gelu_erf(float g) { return 0.5f * g * (1.0f + erff(g * 0
 
 constexpr int GB_BK = 64;             // bf16 elements per K chunk = 128 B per LDS row
 constexpr int GB_ROW_BYTES = 128;
-constexpr u32 BUF_FLAGS = 0x00020000; // raw buffer descriptor word 3 (32-bit data format)
+[[maybe_unused]] constexpr u32 BUF_FLAGS = 0x00020000; // raw buffer descriptor word 3 (32-bit data format)
 
 struct GemmArgs {
   const void *A;        // [rows, K] dispatched rows; with GATHER: x [T, K]
@@ -185,8 +185,8 @@ constexpr int PK_A_STAGE = PK_BM * GB_ROW_BYTES, PK_B_STAGE = PK_BROWS * GB_ROW_
 constexpr int PK_A_STAGES = 2, PK_B_STAGES = 3;
 constexpr int PK_B_BASE = PK_A_STAGES * PK_A_STAGE;
 constexpr int PK_SMEM = PK_B_BASE + PK_B_STAGES * PK_B_STAGE;  // 160 KB: all of a CU's LDS
-constexpr int PK_NI = (PK_BM + PK_BROWS) / 8 / PK_NW;  // 1 KB load instructions per wave per chunk
-constexpr int PK_NIA = PK_BM / 8 / PK_NW;
+[[maybe_unused]] constexpr int PK_NI = (PK_BM + PK_BROWS) / 8 / PK_NW;  // 1 KB load instructions per wave per chunk
+[[maybe_unused]] constexpr int PK_NIA = PK_BM / 8 / PK_NW;
 
 template <bool GATED, int ACT, bool GATHER>
 __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmArgs P) {
