@@ -161,3 +161,68 @@ def test_backward_c2_full_size_per_group_capacity():
 
 def test_backward_c3_full_size():
     _full_size(wl.C3, ("ir", "fr"), 256)
+
+
+def test_forward_backward_random_configurations():
+    """Sixteen seeded draws over shapes, expert counts, k, groups, modes, capacity scope, dtype and
+    activation, through the whole layer and its backward.  Router inputs are small dyadic rationals
+    (exact logits, so the tables must match bit for bit); expert weights are normal."""
+    rng = np.random.default_rng(4242)
+    done = 0
+    while done < 16:
+        G = int(rng.choice([1, 2, 4]))
+        E = G * int(rng.integers(1, 16 // G + 1))
+        k = int(rng.integers(1, 4))
+        if k + 1 > E:
+            continue
+        quota = bool(rng.integers(0, 2))
+        T = G * 128 * int(rng.integers(1, 5)) if quota else G * int(rng.integers(10, 200))
+        d = 8 * int(rng.integers(2, 40))
+        F = 8 * int(rng.integers(2, 64))
+        dtype = "bf16" if rng.integers(0, 2) else "f32"
+        act = "swiglu" if rng.integers(0, 2) else "gelu"
+        mode = MODES[int(rng.integers(0, 4))]
+        cf = float(rng.choice([0.3, 0.75, 1.0, 1.5]))
+        st = bool(rng.integers(0, 2))
+        x = rng.integers(-3, 4, size=(T, d)).astype(np.float32) / np.float32(2.0)
+        wr = rng.integers(-4, 5, size=(E, d)).astype(np.float32) / np.float32(8.0)
+        b = rng.integers(-8, 9, size=E).astype(np.float32) / np.float32(4.0)
+        w1 = wl._store(rng.standard_normal((E, F, d), dtype=np.float32) * np.float32(0.1), dtype)
+        w3 = wl._store(rng.standard_normal((E, F, d), dtype=np.float32) * np.float32(0.1), dtype) if act == "swiglu" else None
+        w2 = wl._store(rng.standard_normal((E, d, F), dtype=np.float32) * np.float32(0.1), dtype)
+        dout = wl._store(rng.standard_normal((T, d), dtype=np.float32), dtype)
+        xs = wl._store(x, dtype)
+        what = f"T={T} d={d} F={F} E={E} G={G} k={k} cf={cf} {dtype} {act} mode={mode} quota={quota} st={st}"
+        cfg = rr.RRConfig(T, d, F, E, k, G, cf, rr.RR_F32 if dtype == "f32" else rr.RR_BF16,
+                          rr.RR_ACT_GELU if act == "gelu" else rr.RR_ACT_SWIGLU, gu.flags_of(mode, False, quota))
+        dev = {"x": gu.to_device(xs, dtype), "w_router": torch.from_numpy(wr).cuda(), "bias": torch.from_numpy(b).cuda(),
+               "w1": gu.to_device(w1, dtype), "w3": gu.to_device(w3, dtype), "w2": gu.to_device(w2, dtype)}
+        tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+        out = torch.empty((T, d), dtype=tdt, device="cuda")
+        logits = torch.empty((T, E), dtype=torch.float32, device="cuda")
+        tb, ws = rr.alloc_tables(cfg), rr.alloc_workspace(cfg)
+        rr.rr_moe_forward(cfg, dev["x"], dev["w_router"], dev["bias"], dev["w1"], dev["w3"], dev["w2"], out, tb, logits, ws)
+        dlogits = torch.empty((T, E), dtype=torch.float32, device="cuda")
+        dcw = torch.empty((T, k + 2), dtype=torch.float32, device="cuda")
+        rr.rr_router_backward(cfg, gu.to_device(dout, dtype), logits, tb, ws, dlogits, dcw, st)
+        torch.cuda.synchronize()
+        f32 = lambda s: None if s is None else wl.values_f32(s, dtype)
+        a = orc.router_scores(f32(xs), wr, b)
+        assert np.array_equal(logits.cpu().numpy(), a), what
+        want = orc.route(a, k, G, cf, "ir" in mode, "fr" in mode, quota=quota)
+        tol = 1e-5 if dtype == "f32" else 2e-2
+        try:
+            gu.assert_tables_equal(tb.to_host(), want, cw_atol=1e-6)
+            want_out = orc.moe_output(f32(xs), want, k, f32(w1), f32(w3), f32(w2), act)
+            err = gu.rel_l2(gu.to_host_f64(out), want_out)
+            assert err <= tol, f"output rel-L2 {err}"
+            want_dc, want_da = orc.router_score_gradient(f32(xs), a, want, k, f32(w1), f32(w3), f32(w2), act, f32(dout),
+                                                         straight_through=st)
+            if np.abs(want_da).max() > 0:  # vanilla top-1 without straight-through: every gradient is zero
+                _check(dcw.cpu().numpy().astype(np.float64), dlogits.cpu().numpy().astype(np.float64), want_dc,
+                       want_da, want, k, tol)
+            else:
+                assert not dlogits.cpu().numpy().any()
+        except AssertionError as err:
+            raise AssertionError(f"{what}: {err}") from None
+        done += 1
