@@ -28,10 +28,13 @@ namespace {
 
 constexpr int TS = kMaxE + 1;  // LDS row stride of a [token][expert] tile
 
+constexpr int kIrSelfMax = 4096;  // experts x token blocks up to which ir_weights does the block scan itself
+
 struct DispatchArgs {
   int T, E, k, C, NR, NCAT, NB, Eg, Tg, ir, fr, arrival, BM, max_mtiles;
   int Cq, Gq, NL;  // capacity blocks: Gq per expert (1, or one per group with per-group quotas) of Cq slots
   int NBc, cb;     // candidate counts come per count block: cb of them per token block, NBc in all
+  int ir_self;     // small batches: ir_weights sums the Intra-GPU block counts itself (no scan launch)
 };
 
 // lanes of this wave whose (valid, e) equals the caller's; e < 64
@@ -576,22 +579,39 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
   const int i = b * kTokBlock + tid;
   const bool valid = i < A.T;
   for (int c = tid; c < NW * kMaxE; c += kTokBlock) (&wcnt[0][0])[c] = 0;
-  // the row plan is a few dozen numbers: every workgroup recomputes the list offsets it needs, the
-  // first one also writes the plan out for the kernels that follow
-  if (w == 0) row_plan_wave(A, blockIdx.x == 0, fill_total, ir_cnt, s_off, ir_offset, row_base, tiles, tile_ctl);
-  __syncthreads();
+  __shared__ int s_cnt[kMaxE], s_before[kMaxE];
+  const bool self = A.ir_self && A.ir;
+  if (self && tid < kMaxE) s_cnt[tid] = s_before[tid] = 0;
   int ndrop = 0;
   if (valid) ndrop = drops_of_token(slot, i, A.k);
   const bool has_ir = valid && A.ir && ndrop > 0;
   const int h = has_ir ? ir_cand[i] : 0;
   unsigned long long mask = same_expert_mask(has_ir, h);
   const int below = lanes_below(mask);
+  __syncthreads();
   if (has_ir && below == 0) wcnt[w][h] = __popcll(mask);
+  // Small batches: ir_blk_off holds the raw per-block counts (at most a few thousand numbers) and
+  // every workgroup adds up what it needs - the tokens of each expert's list in earlier blocks and
+  // in all blocks - instead of a scan launch of its own in front of this kernel.
+  if (self) {
+    for (int idx = tid; idx < A.E * A.NB; idx += kTokBlock) {
+      const int e = idx / A.NB, bb = idx - e * A.NB, v = ir_blk_off[idx];
+      if (v) {
+        atomicAdd(&s_cnt[e], v);
+        if (bb < b) atomicAdd(&s_before[e], v);
+      }
+    }
+    __syncthreads();
+  }
+  // the row plan is a few dozen numbers: every workgroup recomputes the list offsets it needs, the
+  // first one also writes the plan out for the kernels that follow
+  if (w == 0)
+    row_plan_wave(A, blockIdx.x == 0, fill_total, self ? s_cnt : ir_cnt, s_off, ir_offset, row_base, tiles, tile_ctl);
   __syncthreads();
   if (!valid) return;
   float a_h = 0.0f;
   if (has_ir) {
-    int row = ir_blk_off[(size_t)h * A.NB + b] + below;
+    int row = (A.ir_self ? s_before[h] : ir_blk_off[(size_t)h * A.NB + b]) + below;
     for (int q = 0; q < w; ++q) row += wcnt[q][h];
     ir_expert[i] = h;
     ir_row[i] = row;
@@ -637,7 +657,7 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
 hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, bool ranked,
                            hipStream_t s) {
   DispatchArgs A{D.T, D.E, D.k, D.C, D.NR, D.NCAT, D.NB, D.Eg, D.Tg, D.ir, D.fr, D.arrival, D.BM, D.max_mtiles,
-                 D.Cq, D.Gq, D.NL, D.NBc, D.cb};
+                 D.Cq, D.Gq, D.NL, D.NBc, D.cb, D.E * D.NB <= kIrSelfMax ? 1 : 0};
   if (!ranked) {  // otherwise the router's epilogue has already written what topk_rank writes
     prof_begin(K_TOPK, s);
     topk_rank_kernel<<<D.NB, kTokBlock, 0, s>>>(logits, A, tb.rank_expert, tb.slot, W.key, W.ir_score, W.ir_cand,
@@ -659,9 +679,11 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     prof_begin(K_IR_COUNT, s);
     ir_count_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.ir_cand, W.ir_blk_cnt);
     prof_end(K_IR_COUNT, s);
-    prof_begin(K_IR_SCAN, s);
-    scan_blocks_kernel<<<D.E, SC_THREADS, 0, s>>>(W.ir_blk_cnt, W.ir_cnt, D.NB);
-    prof_end(K_IR_SCAN, s);
+    if (!A.ir_self) {
+      prof_begin(K_IR_SCAN, s);
+      scan_blocks_kernel<<<D.E, SC_THREADS, 0, s>>>(W.ir_blk_cnt, W.ir_cnt, D.NB);
+      prof_end(K_IR_SCAN, s);
+    }
   }
   prof_begin(K_IR_WEIGHTS, s);
   ir_weights_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.key, W.ir_score, W.ir_cand, W.ir_blk_cnt, W.ir_cnt,
