@@ -26,10 +26,10 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 
 # Bytes per launch that left the L2s (FETCH_SIZE x 2.0, the factor a 1 GiB copy reads) plus bytes
 # written (WRITE_SIZE x 1.0), from two rocprofv3 --pmc runs of this benchmark; see
-# profiles/bench_c2_forward_hbm_traffic.md.  Keyed by (workload, kernel); None where not measured.
+# profiles/bench_forward_hbm_traffic.md.  Keyed by (workload, kernel); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    ("c2_top1_bf16_zipf1.1", "ffn_gate_up"): 1967.9e6 + 114.7e6,
-    ("c2_top1_bf16_zipf1.1", "ffn_down"): 815.1e6 + 42.1e6,
+    ("c2_top1_bf16_zipf1.1", "ffn_gate_up"): 1841.4e6 + 114.8e6,
+    ("c2_top1_bf16_zipf1.1", "ffn_down"): 809.6e6 + 41.8e6,
 }
 
 
