@@ -28,6 +28,7 @@ namespace {
 
 constexpr int TS = kMaxE + 1;  // LDS row stride of a [token][expert] tile
 
+constexpr int kDirectMaxT = 16384;  // tokens up to which the selection lists are not materialised (see select_direct_kernel)
 constexpr int kIrSelfMax = 4096;  // experts x token blocks up to which ir_weights does the block scan itself
 
 struct DispatchArgs {
@@ -35,6 +36,7 @@ struct DispatchArgs {
   int Cq, Gq, NL;  // capacity blocks: Gq per expert (1, or one per group with per-group quotas) of Cq slots
   int NBc, cb;     // candidate counts come per count block: cb of them per token block, NBc in all
   int ir_self;     // small batches: ir_weights sums the Intra-GPU block counts itself (no scan launch)
+  int direct;      // small batches, one capacity block per expert: select_direct_kernel finds its candidates itself
 };
 
 // lanes of this wave whose (valid, e) equals the caller's; e < 64
@@ -480,6 +482,145 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
     for (int sl = fill0 + m + tid; sl < (g + 1) * A.Cq; sl += SS_THREADS) slot_token[(size_t)j * A.C + sl] = -1;
 }
 
+// ------------------------------------------------------------------ select_slot, small batches
+// Up to SS_THREADS * SS_PER tokens and one capacity block per expert: the workgroup of list
+// (round r, expert j) finds its candidates itself - it reads column r of rank_expert for every token,
+// idx = u * SS_THREADS + tid being element u of thread tid, so candidates are met in token order -
+// and counts expert j's candidates of the earlier rounds on the way (the kept count of a round is
+// min(candidates, free slots)).  No candidate counts, no scan, no scatter: three launches fewer.
+// The selection itself is that of select_slot_kernel's register path.
+__global__ __launch_bounds__(SS_THREADS) void select_direct_kernel(DispatchArgs A,
+                                                                   const int32_t *__restrict__ rank_expert,
+                                                                   const u32 *__restrict__ key,
+                                                                   int32_t *__restrict__ slot,
+                                                                   int32_t *__restrict__ slot_token,
+                                                                   int32_t *__restrict__ grp_fill,
+                                                                   int32_t *__restrict__ grp_off,
+                                                                   int32_t *__restrict__ fill_topk,
+                                                                   int32_t *__restrict__ fill_total) {
+  __shared__ u32 hist[256];
+  __shared__ u32 s_pick[2];
+  __shared__ int2 wtot[SS_PER][SS_WAVES];
+  __shared__ int2 wsum[8];
+  __shared__ int s_cnt[kMaxRounds];
+  const int r = blockIdx.x / A.E, j = blockIdx.x - r * A.E;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int nu = (A.T + SS_THREADS - 1) / SS_THREADS;
+  if (tid < kMaxRounds) s_cnt[tid] = 0;
+  __syncthreads();
+  u32 member = 0;  // bit u: token u * SS_THREADS + tid is a candidate of this list
+  int c_rr[kMaxRounds];
+#pragma unroll
+  for (int rr = 0; rr < kMaxRounds; ++rr) c_rr[rr] = 0;
+#pragma unroll
+  for (int u = 0; u < SS_PER; ++u) {
+    const int idx = u * SS_THREADS + tid;
+    if (u < nu && idx < A.T) {
+#pragma unroll
+      for (int rr = 0; rr < kMaxRounds; ++rr)
+        if (rr <= r && rank_expert[(size_t)idx * (A.k + 1) + rr] == j) {
+          ++c_rr[rr];
+          if (rr == r) member |= 1u << u;
+        }
+    }
+  }
+#pragma unroll
+  for (int rr = 0; rr < kMaxRounds; ++rr) {
+    if (rr <= r) {  // r is uniform over the workgroup
+      int v = c_rr[rr];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
+      if (lane == 0 && v) atomicAdd(&s_cnt[rr], v);
+    }
+  }
+  __syncthreads();
+  int n = 0, m = 0, fill = 0, topk = 0;
+  for (int rr = 0; rr <= r; ++rr) {
+    fill += m;
+    n = s_cnt[rr];
+    m = min(n, A.Cq - fill);
+    if (rr == A.k - 1) topk = fill + m;
+  }
+  const int fill0 = fill;
+  if (r == A.NR - 1 && tid == 0) {  // the expert's last round also writes its fill counts
+    grp_fill[j] = fill + m;
+    grp_off[j] = 0;
+    fill_total[j] = fill + m;
+    fill_topk[j] = topk;
+  }
+  const bool by_score = !A.arrival || r == A.k;  // the Fill-in round always selects by score (Sec. 4.2)
+  const unsigned long long below = (1ull << lane) - 1ull;
+  // mode 0: nobody kept; 1: everybody kept; 2: the first m in token order; 3: by score threshold
+  const int mode = m == 0 ? 0 : (m == n ? 1 : (by_score ? 3 : 2));
+  u32 thr = 0, need_eq = 0;
+  u32 kreg[SS_PER];
+#pragma unroll
+  for (int u = 0; u < SS_PER; ++u) {
+    kreg[u] = 0;
+    if (mode == 3 && ((member >> u) & 1u)) kreg[u] = key[(size_t)(u * SS_THREADS + tid) * A.NR + r];
+  }
+  if (mode == 3)
+    thr = radix_select(m, [&](auto f) {
+#pragma unroll
+      for (int u = 0; u < SS_PER; ++u)
+        if ((member >> u) & 1u) f(kreg[u]);
+    }, hist, s_pick, need_eq);
+  if (mode == 2) need_eq = (u32)m;  // arrival order: every candidate "ties", the first m of them are kept
+
+  int pre[SS_PER];  // lanes of this wave before this one: kept-for-sure | equal << 8
+#pragma unroll
+  for (int u = 0; u < SS_PER; ++u) {
+    pre[u] = 0;
+    if (u < nu) {
+      const bool cand = (member >> u) & 1u;
+      bool gt = false, eq = false;
+      if (mode == 3) { gt = cand && kreg[u] > thr; eq = cand && kreg[u] == thr; }
+      else if (mode == 2) eq = cand;
+      else gt = cand && mode == 1;
+      const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+      pre[u] = __popcll(bgt & below) | (__popcll(beq & below) << 8) | (gt ? 1 << 16 : 0) | (eq ? 1 << 17 : 0);
+      if (lane == 0) wtot[u][w] = make_int2(__popcll(bgt), __popcll(beq));
+    }
+  }
+  __syncthreads();
+  // exclusive scan of the nu * SS_WAVES totals in (trip, wave) order = token order
+  const int ne = nu * SS_WAVES;
+  int2 mine = make_int2(0, 0), incl = mine;
+  if (tid < ne) mine = (&wtot[0][0])[tid];
+  if (tid < 8 * kWave) {
+    incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int tx = __shfl_up(incl.x, off), ty = __shfl_up(incl.y, off);
+      if (lane >= off) { incl.x += tx; incl.y += ty; }
+    }
+    if (lane == 63) wsum[w] = incl;
+  }
+  __syncthreads();
+  if (tid < ne) {
+    int2 before = make_int2(0, 0);
+    for (int q = 0; q < w; ++q) { before.x += wsum[q].x; before.y += wsum[q].y; }
+    (&wtot[0][0])[tid] = make_int2(before.x + incl.x - mine.x, before.y + incl.y - mine.y);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < SS_PER; ++u) {
+    if (u < nu && ((member >> u) & 1u)) {
+      const int tok = u * SS_THREADS + tid;
+      const int2 base = wtot[u][w];
+      const bool gt = (pre[u] >> 16) & 1, eq = (pre[u] >> 17) & 1;
+      const int eqs = base.y + ((pre[u] >> 8) & 255);  // equal keys before this one
+      const bool kept = gt || (eq && (u32)eqs < need_eq);
+      const int sl = fill0 + base.x + (pre[u] & 255) + min(eqs, (int)need_eq);
+      slot[(size_t)tok * (A.k + 1) + r] = kept ? sl : -1;
+      if (kept) slot_token[(size_t)j * A.C + sl] = tok;
+    }
+  }
+  // the last round pads the rest of the queue (Sec. 3: zero padding)
+  if (r == A.NR - 1)
+    for (int sl = fill0 + m + tid; sl < A.Cq; sl += SS_THREADS) slot_token[(size_t)j * A.C + sl] = -1;
+}
+
 // ------------------------------------------------------------------ Intra-GPU lists
 __device__ inline int drops_of_token(const int32_t *slot, int i, int k) {
   int n = 0;
@@ -657,24 +798,32 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
 hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, bool ranked,
                            hipStream_t s) {
   DispatchArgs A{D.T, D.E, D.k, D.C, D.NR, D.NCAT, D.NB, D.Eg, D.Tg, D.ir, D.fr, D.arrival, D.BM, D.max_mtiles,
-                 D.Cq, D.Gq, D.NL, D.NBc, D.cb, D.E * D.NB <= kIrSelfMax ? 1 : 0};
+                 D.Cq, D.Gq, D.NL, D.NBc, D.cb, D.E * D.NB <= kIrSelfMax ? 1 : 0,
+                 D.Gq == 1 && D.T <= kDirectMaxT ? 1 : 0};
   if (!ranked) {  // otherwise the router's epilogue has already written what topk_rank writes
     prof_begin(K_TOPK, s);
     topk_rank_kernel<<<D.NB, kTokBlock, 0, s>>>(logits, A, tb.rank_expert, tb.slot, W.key, W.ir_score, W.ir_cand,
                                                 W.blk_cnt);
     prof_end(K_TOPK, s);
   }
-  prof_begin(K_SCAN_CAND, s);
-  scan_blocks_kernel<<<D.NCAT, SC_THREADS, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NBc);
-  prof_end(K_SCAN_CAND, s);
-  prof_begin(K_SCATTER_CAND, s);
-  scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_cnt, W.cand_key,
-                                                       W.cand_tok);
-  prof_end(K_SCATTER_CAND, s);
-  prof_begin(K_SELECT_SLOT, s);
-  select_slot_kernel<<<D.NL, SS_THREADS, 0, s>>>(A, W.cat_cnt, W.blk_cnt, W.cand_key, W.cand_tok, tb.slot,
-                                                 tb.slot_token, W.grp_fill, W.grp_off, tb.fill_topk, tb.fill_total);
-  prof_end(K_SELECT_SLOT, s);
+  if (A.direct) {
+    prof_begin(K_SELECT_SLOT, s);
+    select_direct_kernel<<<D.NCAT, SS_THREADS, 0, s>>>(A, tb.rank_expert, W.key, tb.slot, tb.slot_token, W.grp_fill,
+                                                       W.grp_off, tb.fill_topk, tb.fill_total);
+    prof_end(K_SELECT_SLOT, s);
+  } else {
+    prof_begin(K_SCAN_CAND, s);
+    scan_blocks_kernel<<<D.NCAT, SC_THREADS, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NBc);
+    prof_end(K_SCAN_CAND, s);
+    prof_begin(K_SCATTER_CAND, s);
+    scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_cnt, W.cand_key,
+                                                         W.cand_tok);
+    prof_end(K_SCATTER_CAND, s);
+    prof_begin(K_SELECT_SLOT, s);
+    select_slot_kernel<<<D.NL, SS_THREADS, 0, s>>>(A, W.cat_cnt, W.blk_cnt, W.cand_key, W.cand_tok, tb.slot,
+                                                   tb.slot_token, W.grp_fill, W.grp_off, tb.fill_topk, tb.fill_total);
+    prof_end(K_SELECT_SLOT, s);
+  }
   if (D.ir) {
     prof_begin(K_IR_COUNT, s);
     ir_count_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.ir_cand, W.ir_blk_cnt);
