@@ -141,6 +141,66 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4 *__restrict__ 
   }
 }
 
+// The same sum with one wave per token and no LDS: lane p fetches the row and weight of assignment p,
+// the wave broadcasts them, every lane then strides over the 16-byte vectors of the rows.
+template <bool BF16>
+__global__ __launch_bounds__(256) void combine_wave_kernel(const uint4 *__restrict__ y, uint4 *__restrict__ out,
+                                                           int vec_per_row, int T, int k, int NR,
+                                                           const int32_t *__restrict__ rank_expert,
+                                                           const int32_t *__restrict__ slot,
+                                                           const int32_t *__restrict__ ir_expert,
+                                                           const int32_t *__restrict__ ir_row,
+                                                           const int32_t *__restrict__ fill_total,
+                                                           const int32_t *__restrict__ row_base,
+                                                           const int32_t *__restrict__ grp_off, int Cq, int Gq,
+                                                           const float *__restrict__ combine_w) {
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= T) return;
+  const int lane = lane_id();
+  int my_row = -1;
+  float my_w = 0.0f;
+  if (lane < NR) {
+    const int s = slot[(size_t)i * (k + 1) + lane];
+    if (s >= 0) {
+      const int e = rank_expert[(size_t)i * (k + 1) + lane], g = s / Cq;
+      my_row = row_base[e] + grp_off[e * Gq + g] + (s - g * Cq);
+      my_w = combine_w[(size_t)i * (k + 2) + lane];
+    }
+  } else if (lane == kMaxRank) {
+    const int h = ir_expert[i];
+    if (h >= 0) {
+      my_row = row_base[h] + fill_total[h] + ir_row[i];
+      my_w = combine_w[(size_t)i * (k + 2) + k + 1];
+    }
+  }
+  int row[kMaxRank + 1];
+  float wgt[kMaxRank + 1];
+#pragma unroll
+  for (int p = 0; p <= kMaxRank; ++p) {
+    row[p] = __shfl(my_row, p, kWave);
+    wgt[p] = __shfl(my_w, p, kWave);
+  }
+  for (int v = lane; v < vec_per_row; v += kWave) {
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p <= kMaxRank; ++p)
+      if (row[p] >= 0) fma_row(acc, wgt[p], y[(size_t)row[p] * vec_per_row + v], BF16);
+    uint4 o;
+    if (BF16) {
+      o.x = f32_to_bf16_rne(acc[0]) | (f32_to_bf16_rne(acc[1]) << 16);
+      o.y = f32_to_bf16_rne(acc[2]) | (f32_to_bf16_rne(acc[3]) << 16);
+      o.z = f32_to_bf16_rne(acc[4]) | (f32_to_bf16_rne(acc[5]) << 16);
+      o.w = f32_to_bf16_rne(acc[6]) | (f32_to_bf16_rne(acc[7]) << 16);
+    } else {
+      o.x = __builtin_bit_cast(u32, acc[0]);
+      o.y = __builtin_bit_cast(u32, acc[1]);
+      o.z = __builtin_bit_cast(u32, acc[2]);
+      o.w = __builtin_bit_cast(u32, acc[3]);
+    }
+    out[(size_t)i * vec_per_row + v] = o;
+  }
+}
+
 }  // namespace
 
 hipError_t launch_gather(const Dims &D, const void *x, const rr_tables &tb, const Work &W, hipStream_t s) {
@@ -164,14 +224,28 @@ hipError_t launch_combine(const Dims &D, const rr_tables &tb, const Work &W, voi
   const int es = D.dtype == RR_BF16 ? 2 : 4;
   const int vec_per_row = D.d * es / 16;
   prof_begin(K_COMBINE, s);
-  if (D.dtype == RR_BF16)
-    combine_kernel<true><<<D.T, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out), vec_per_row,
-                                             D.k, D.NR, tb.rank_expert, tb.slot, tb.ir_expert, tb.ir_row,
-                                             tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w);
-  else
-    combine_kernel<false><<<D.T, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out), vec_per_row,
-                                              D.k, D.NR, tb.rank_expert, tb.slot, tb.ir_expert, tb.ir_row,
-                                              tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w);
+  // rows of up to 4 KB: one wave per token (no LDS, no barrier); longer rows: one workgroup per token
+  if (vec_per_row <= 256) {
+    if (D.dtype == RR_BF16)
+      combine_wave_kernel<true><<<(D.T + 3) / 4, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out),
+                                                              vec_per_row, D.T, D.k, D.NR, tb.rank_expert, tb.slot,
+                                                              tb.ir_expert, tb.ir_row, tb.fill_total, W.row_base, W.grp_off,
+                                                              D.Cq, D.Gq, tb.combine_w);
+    else
+      combine_wave_kernel<false><<<(D.T + 3) / 4, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out),
+                                                               vec_per_row, D.T, D.k, D.NR, tb.rank_expert, tb.slot,
+                                                               tb.ir_expert, tb.ir_row, tb.fill_total, W.row_base,
+                                                               W.grp_off, D.Cq, D.Gq, tb.combine_w);
+  } else {
+    if (D.dtype == RR_BF16)
+      combine_kernel<true><<<D.T, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out), vec_per_row,
+                                               D.k, D.NR, tb.rank_expert, tb.slot, tb.ir_expert, tb.ir_row,
+                                               tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w);
+    else
+      combine_kernel<false><<<D.T, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out), vec_per_row,
+                                                D.k, D.NR, tb.rank_expert, tb.slot, tb.ir_expert, tb.ir_row,
+                                                tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w);
+  }
   prof_end(K_COMBINE, s);
   return hipGetLastError();
 }
