@@ -509,13 +509,16 @@ __global__ __launch_bounds__(SS_THREADS) void select_direct_kernel(DispatchArgs 
   if (tid < kMaxRounds) s_cnt[tid] = 0;
   __syncthreads();
   u32 member = 0;  // bit u: token u * SS_THREADS + tid is a candidate of this list
+  u32 kreg[SS_PER];  // score keys of round r, fetched for every token in the same round trip as the ranks
   int c_rr[kMaxRounds];
 #pragma unroll
   for (int rr = 0; rr < kMaxRounds; ++rr) c_rr[rr] = 0;
 #pragma unroll
   for (int u = 0; u < SS_PER; ++u) {
     const int idx = u * SS_THREADS + tid;
+    kreg[u] = 0;
     if (u < nu && idx < A.T) {
+      kreg[u] = key[(size_t)idx * A.NR + r];
 #pragma unroll
       for (int rr = 0; rr < kMaxRounds; ++rr)
         if (rr <= r && rank_expert[(size_t)idx * (A.k + 1) + rr] == j) {
@@ -553,12 +556,6 @@ __global__ __launch_bounds__(SS_THREADS) void select_direct_kernel(DispatchArgs 
   // mode 0: nobody kept; 1: everybody kept; 2: the first m in token order; 3: by score threshold
   const int mode = m == 0 ? 0 : (m == n ? 1 : (by_score ? 3 : 2));
   u32 thr = 0, need_eq = 0;
-  u32 kreg[SS_PER];
-#pragma unroll
-  for (int u = 0; u < SS_PER; ++u) {
-    kreg[u] = 0;
-    if (mode == 3 && ((member >> u) & 1u)) kreg[u] = key[(size_t)(u * SS_THREADS + tid) * A.NR + r];
-  }
   if (mode == 3)
     thr = radix_select(m, [&](auto f) {
 #pragma unroll
@@ -723,10 +720,29 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
   __shared__ int s_cnt[kMaxE], s_before[kMaxE];
   const bool self = A.ir_self && A.ir;
   if (self && tid < kMaxE) s_cnt[tid] = s_before[tid] = 0;
-  int ndrop = 0;
-  if (valid) ndrop = drops_of_token(slot, i, A.k);
+  // everything this token needs from global memory is fetched here, in one round trip, ahead of the
+  // barriers (loads do not move across them)
+  int slot_r[kMaxRank], cand = 0, ndrop = 0;
+  u32 key_r[kMaxRank];
+  float score_h = 0.0f;
+#pragma unroll
+  for (int r = 0; r < kMaxRank; ++r) {
+    slot_r[r] = -1;
+    key_r[r] = 0;
+    if (valid && r < A.NR) {
+      slot_r[r] = slot[(size_t)i * (A.k + 1) + r];
+      key_r[r] = key[(size_t)i * A.NR + r];
+    }
+  }
+  if (valid && A.ir) {
+    cand = ir_cand[i];
+    score_h = ir_score[i];
+  }
+#pragma unroll
+  for (int r = 0; r < kMaxRank; ++r)
+    if (r < A.k) ndrop += slot_r[r] < 0;
   const bool has_ir = valid && A.ir && ndrop > 0;
-  const int h = has_ir ? ir_cand[i] : 0;
+  const int h = has_ir ? cand : 0;
   unsigned long long mask = same_expert_mask(has_ir, h);
   const int below = lanes_below(mask);
   __syncthreads();
@@ -757,7 +773,7 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
     ir_expert[i] = h;
     ir_row[i] = row;
     ir_token[s_off[h] + row] = i;
-    a_h = ir_score[i];
+    a_h = score_h;
   } else {
     ir_expert[i] = -1;
     ir_row[i] = -1;
@@ -772,9 +788,9 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
     kept[r] = false;
     a_r[r] = 0.0f;
     if (r < A.NR) {
-      kept[r] = slot[(size_t)i * (A.k + 1) + r] >= 0;
+      kept[r] = slot_r[r] >= 0;
       if (kept[r]) {
-        a_r[r] = key_score(key[(size_t)i * A.NR + r]);
+        a_r[r] = key_score(key_r[r]);
         mx = fmaxf(mx, a_r[r]);
       }
     }
