@@ -195,6 +195,19 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
   const int i = b * kTokBlock + tid;
   const bool valid = i < A.T;
   for (int c = tid; c < kMaxRounds * NW * kMaxE; c += kTokBlock) (&wcnt[0][0][0])[c] = 0;
+  // the token's own data is fetched in the same round trip as the array counts below (loads do not
+  // move across barriers by themselves)
+  int e_r[kMaxRounds], rank_r[kMaxRounds], off_r[kMaxRounds];
+  u32 key_r[kMaxRounds];
+#pragma unroll
+  for (int r = 0; r < kMaxRounds; ++r) {
+    e_r[r] = 0;
+    key_r[r] = 0;
+    if (valid && r < A.NR) {
+      e_r[r] = rank_expert[(size_t)i * (A.k + 1) + r];
+      key_r[r] = key[(size_t)i * A.NR + r];
+    }
+  }
   // every token is a candidate of exactly one array per round: round r's arrays tile [r T, (r+1) T)
   // in expert order (a dozen counts: recomputed by every workgroup rather than by a launch of its own)
   for (int r = w; r < A.NR; r += NW) {
@@ -208,17 +221,16 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
     if (lane < A.E) s_base[r * A.E + lane] = r * A.T + incl - c;
   }
   __syncthreads();
-  int e_r[kMaxRounds], rank_r[kMaxRounds];
 #pragma unroll
   for (int r = 0; r < kMaxRounds; ++r) {
-    e_r[r] = 0;
     rank_r[r] = 0;
+    off_r[r] = 0;
     if (r < A.NR) {
-      int e = valid ? rank_expert[(size_t)i * (A.k + 1) + r] : 0;
+      const int e = e_r[r];
+      if (valid) off_r[r] = blk_off[(size_t)(r * A.E + e) * A.NBc + b * A.cb];  // in flight across the barrier
       unsigned long long mask = same_expert_mask(valid, e);
       int below = lanes_below(mask);
       if (valid && below == 0) wcnt[r][w][e] = __popcll(mask);
-      e_r[r] = e;
       rank_r[r] = below;
     }
   }
@@ -228,9 +240,9 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
   for (int r = 0; r < kMaxRounds; ++r) {
     if (r < A.NR) {
       int e = e_r[r], cat = r * A.E + e;
-      int pos = s_base[cat] + blk_off[(size_t)cat * A.NBc + b * A.cb] + rank_r[r];
+      int pos = s_base[cat] + off_r[r] + rank_r[r];
       for (int q = 0; q < w; ++q) pos += wcnt[r][q][e];
-      cand_key[pos] = key[(size_t)i * A.NR + r];
+      cand_key[pos] = key_r[r];
       cand_tok[pos] = i;
     }
   }
