@@ -455,8 +455,9 @@ def test_quota_forward_c5_full_size():
 
 # ------------------------------------------------------------------ seeded random configurations
 def test_dispatch_random_configurations():
-    """Sixty seeded draws over the whole argument space of the routing tables (sizes, E, G, k, capacity
-    factor, rectification modes, drop policy, capacity scope, tie density): tables bit-exact."""
+    """Sixty seeded draws over the whole argument space of the routing tables (sizes on both sides of
+    the small-batch path's limit, E, G, k, capacity factor, rectification modes, drop policy, capacity
+    scope, tie density): tables bit-exact."""
     rng = np.random.default_rng(2024)
     done = 0
     while done < 60:
@@ -468,6 +469,8 @@ def test_dispatch_random_configurations():
         quota = bool(rng.integers(0, 2))
         if quota:
             T = G * 128 * int(rng.integers(1, 12))
+        elif rng.integers(0, 4) == 0:  # above 16 K tokens the selection lists are materialised (scan, scatter)
+            T = G * int(rng.integers(16384 // G + 1, 40000 // G))
         else:
             T = G * int(rng.integers(1, 1500))
         mode = MODES[int(rng.integers(0, 4))]
