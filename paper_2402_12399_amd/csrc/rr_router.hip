@@ -126,6 +126,54 @@ __device__ inline void rank_row(const float *row, int tok, int E, int k, int32_t
   }
 }
 
+// The same per-token results as rank_row from a [tokens][experts] tile in LDS, with every thread
+// of the workgroup at work: the thread of (token, expert e) counts the experts that beat e - a
+// greater score, or an equal one at a lower index (Eq. 1 argtopk, ties -> lower expert index) - and
+// that count is e's rank; the same count inside the token's own group finds the best local expert
+// (Sec. 4.1).  E^2 comparisons per token instead of E insertion steps, but no serial chain: the
+// small-batch kernel's epilogue is latency, not arithmetic.
+template <bool FUSE>
+__device__ inline void rank_tile(const float *tile, int TS, int ntok, int t0, int E, int k, int32_t *rank_expert,
+                                 const RankOut &R, int *cnt) {
+  const int n = min(k + 1, E);
+  int32_t *ranks = FUSE ? R.rank_expert : rank_expert;
+  for (int idx = threadIdx.x; idx < ntok * E; idx += RT_THREADS) {
+    const int row = idx / E, e = idx - row * E, tok = t0 + row;
+    const float *a = tile + row * TS;
+    const float v = a[e];
+    int rank = 0;
+    for (int o = 0; o < E; ++o) {
+      const float x = a[o];
+      rank += (x > v) || (x == v && o < e);
+    }
+    if (rank < n) {
+      ranks[(size_t)tok * (k + 1) + rank] = e;
+      if (FUSE && rank < R.NR) {
+        R.key[(size_t)tok * R.NR + rank] = score_key(v);
+        atomicAdd(&cnt[rank * E + e], 1);
+      }
+    }
+    if (e == 0) {
+      for (int q = n; q <= k; ++q) ranks[(size_t)tok * (k + 1) + q] = -1;
+      if (FUSE && !R.fr) R.slot[(size_t)tok * (k + 1) + k] = -1;
+    }
+    if (FUSE) {
+      const int g = tok / R.Tg, e0 = g * R.Eg;
+      if (e >= e0 && e < e0 + R.Eg) {
+        int before = 0;
+        for (int o = e0; o < e0 + R.Eg; ++o) {
+          const float x = a[o];
+          before += (x > v) || (x == v && o < e);
+        }
+        if (before == 0) {
+          R.ir_score[tok] = v;
+          R.ir_cand[tok] = e;
+        }
+      }
+    }
+  }
+}
+
 template <bool BF16, int TM, int NJ, bool FUSE>
 __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restrict__ xv, const float *__restrict__ wr,
                                                             const float *__restrict__ bias, float *__restrict__ logits,
@@ -283,8 +331,11 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
       row_max[tid] = m;
       row_inv[tid] = 1.0f / s;
     }
-    if (rank_expert || FUSE) rank_row<FUSE>(row, t0 + tid, E, k, rank_expert, R, cnt);
+    // more than 16 experts: one lane per token (the E^2 comparisons of rank_tile then cost more
+    // than the serial insertion saves)
+    if ((rank_expert || FUSE) && E > 16) rank_row<FUSE>(row, t0 + tid, E, k, rank_expert, R, cnt);
   }
+  if ((rank_expert || FUSE) && E <= 16) rank_tile<FUSE>(tile, TS, ntok, t0, E, k, rank_expert, R, cnt);
   if (probs || FUSE) __syncthreads();
   if (probs) {
     for (int idx = tid; idx < ntok * E; idx += RT_THREADS) {
