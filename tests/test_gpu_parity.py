@@ -523,3 +523,49 @@ def test_routing_only_forward_random_configurations():
         except AssertionError as err:
             raise AssertionError(f"T={T} d={d} E={E} G={G} k={k} cf={cf} {dtype} quota={quota}: {err}") from None
         done += 1
+
+
+def test_forward_random_grouped_gemm_shapes():
+    """Twelve seeded draws of bf16 layer shapes that take the LDS-DMA grouped GEMM (d_model and d_ff
+    multiples of 64 from 192 up: ragged row tiles, column tiles narrower than the tile, few or many
+    chunks per tile), over expert counts, k, modes, capacity scope and both activations.  Router
+    inputs are small dyadic rationals, so logits and tables must match bit for bit."""
+    rng = np.random.default_rng(5)
+    done = 0
+    while done < 12:
+        G = int(rng.choice([1, 2, 4]))
+        E = G * int(rng.integers(1, 16 // G + 1))
+        k = int(rng.integers(1, 4))
+        if k + 1 > E:
+            continue
+        quota = bool(rng.integers(0, 2))
+        T = G * 128 * int(rng.integers(1, 17)) if quota else G * int(rng.integers(50, 2500))
+        d = 64 * int(rng.integers(3, 17))
+        F = 64 * int(rng.integers(3, 33))
+        act = "swiglu" if rng.integers(0, 2) else "gelu"
+        mode = MODES[int(rng.integers(0, 4))]
+        cf = float(rng.choice([0.3, 0.75, 1.0, 1.5, 3.0]))
+        x = rng.integers(-3, 4, size=(T, d)).astype(np.float32) / np.float32(2.0)
+        wr = rng.integers(-4, 5, size=(E, d)).astype(np.float32) / np.float32(8.0)
+        b = rng.integers(-8, 9, size=E).astype(np.float32) / np.float32(4.0)
+        w1 = wl._store(rng.standard_normal((E, F, d), dtype=np.float32) * np.float32(0.05), "bf16")
+        w3 = wl._store(rng.standard_normal((E, F, d), dtype=np.float32) * np.float32(0.05), "bf16") if act == "swiglu" else None
+        w2 = wl._store(rng.standard_normal((E, d, F), dtype=np.float32) * np.float32(0.05), "bf16")
+        xs = wl._store(x, "bf16")
+        what = f"T={T} d={d} F={F} E={E} G={G} k={k} cf={cf} {act} mode={mode} quota={quota}"
+        cfg = rr.RRConfig(T, d, F, E, k, G, cf, rr.RR_BF16, rr.RR_ACT_GELU if act == "gelu" else rr.RR_ACT_SWIGLU,
+                          gu.flags_of(mode, False, quota))
+        dev = {"x": gu.to_device(xs, "bf16"), "w_router": torch.from_numpy(wr).cuda(), "bias": torch.from_numpy(b).cuda(),
+               "w1": gu.to_device(w1, "bf16"), "w3": gu.to_device(w3, "bf16"), "w2": gu.to_device(w2, "bf16")}
+        out, tables, logits = gu.run_forward(cfg, dev)
+        f32 = lambda s: None if s is None else wl.values_f32(s, "bf16")
+        a = orc.router_scores(f32(xs), wr, b)
+        assert np.array_equal(logits, a), what
+        want = orc.route(a, k, G, cf, "ir" in mode, "fr" in mode, quota=quota)
+        try:
+            gu.assert_tables_equal(tables, want, cw_atol=1e-6)
+            err = gu.rel_l2(gu.to_host_f64(out), orc.moe_output(f32(xs), want, k, f32(w1), f32(w3), f32(w2), act))
+            assert err <= 2e-2, f"rel-L2 {err}"
+        except AssertionError as err:
+            raise AssertionError(f"{what}: {err}") from None
+        done += 1
