@@ -95,6 +95,10 @@ typedef struct rr_tables {
                                    processed by any expert                                         */
 } rr_tables;
 
+/* Alignment: x, the expert weights, out, dout, w_router, logits and probs must be 16-byte aligned
+ * (rows are moved with 16-byte vector instructions), every other array 4-byte aligned, the workspace
+ * 256-byte aligned; a misaligned pointer is RR_ERR_INVALID_ARG (workspace: RR_ERR_WORKSPACE). */
+
 /* Sec. 3: capacity = capacity factor x tokens / experts, rounded up, at least 1.
  * Evaluated as ceil((double)cf * T / E).  Host function; returns -1 on invalid arguments. */
 int32_t rr_capacity(int32_t T, int32_t E, float capacity_factor);

@@ -144,6 +144,17 @@ static size_t carve(const Dims &D, bool forward, void *ws, Work *W) {
   return cv.off;
 }
 
+// The kernels read and write rows with 16-byte vector instructions: data pointers must be 16-byte
+// aligned (row lengths already are: d_model, d_ff % 8 == 0, E floats per row are accessed 4-byte
+// wise unless the row itself is a multiple of 16 bytes).  NULL (optional arguments) passes.
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+static bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
+static bool tables_aligned(const rr_tables *t) {
+  return aligned4(t->rank_expert) && aligned4(t->slot) && aligned4(t->slot_token) && aligned4(t->fill_topk) &&
+         aligned4(t->fill_total) && aligned4(t->ir_expert) && aligned4(t->ir_row) && aligned4(t->ir_offset) &&
+         aligned4(t->ir_token) && aligned4(t->combine_w);
+}
+
 static bool tables_complete(const rr_tables *t) {
   return t && t->rank_expert && t->slot && t->slot_token && t->fill_topk && t->fill_total && t->ir_expert &&
          t->ir_row && t->ir_offset && t->ir_token && t->combine_w;
@@ -194,6 +205,9 @@ int rr_router_scores(const rr_config *cfg, const void *x, const float *w_router,
   int rc = make_dims(cfg, false, &D);
   if (rc != RR_OK) return rc;
   if (!x || !w_router || !logits) return RR_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(w_router) || !aligned16(logits) || !aligned16(probs) || !aligned4(bias) ||
+      !aligned4(rank_expert))
+    return RR_ERR_INVALID_ARG;
   hipError_t e = launch_router(D, x, w_router, bias, logits, probs, rank_expert, nullptr, nullptr,
                                static_cast<hipStream_t>(stream));
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
@@ -205,6 +219,7 @@ int rr_rectified_dispatch(const rr_config *cfg, const float *logits, const rr_ta
   int rc = make_dims(cfg, false, &D);
   if (rc != RR_OK) return rc;
   if (!logits || !tables_complete(out)) return RR_ERR_INVALID_ARG;
+  if (!aligned16(logits) || !tables_aligned(out)) return RR_ERR_INVALID_ARG;
   Work W;
   memset(&W, 0, sizeof(W));
   rc = check_ws(D, false, workspace, workspace_bytes, &W);
@@ -228,7 +243,9 @@ int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, c
     if (!w1 || !w2 || !out) return RR_ERR_INVALID_ARG;
     if (cfg->act == RR_ACT_SWIGLU && !w3) return RR_ERR_INVALID_ARG;
   }
-  if (tables && !tables_complete(tables)) return RR_ERR_INVALID_ARG;
+  if (tables && (!tables_complete(tables) || !tables_aligned(tables))) return RR_ERR_INVALID_ARG;
+  if (!aligned16(x) || !aligned16(w_router) || !aligned4(bias) || !aligned16(logits)) return RR_ERR_INVALID_ARG;
+  if (!routing_only && (!aligned16(w1) || !aligned16(w3) || !aligned16(w2) || !aligned16(out))) return RR_ERR_INVALID_ARG;
   Work W;
   memset(&W, 0, sizeof(W));
   rc = check_ws(D, !routing_only, workspace, workspace_bytes, &W);
@@ -256,7 +273,8 @@ int rr_router_backward(const rr_config *cfg, const void *dout, const float *logi
   if (rc != RR_OK) return rc;
   if (!dout || !dlogits) return RR_ERR_INVALID_ARG;
   if (grad_flags & ~(uint32_t)RR_GRAD_STRAIGHT_THROUGH) return RR_ERR_INVALID_ARG;
-  if (tables && !tables_complete(tables)) return RR_ERR_INVALID_ARG;
+  if (tables && (!tables_complete(tables) || !tables_aligned(tables))) return RR_ERR_INVALID_ARG;
+  if (!aligned16(dout) || !aligned4(logits) || !aligned4(dcombine_w) || !aligned4(dlogits)) return RR_ERR_INVALID_ARG;
   Work W;
   memset(&W, 0, sizeof(W));
   rc = check_ws(D, true, workspace, workspace_bytes, &W);

@@ -140,6 +140,20 @@ def test_entry_points_reject_bad_arguments_on_the_host(lib):
     assert lib.rr_moe_forward(C.byref(bad), fake, fake, None, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == INVALID
     nofnn = _cfg(d_ff=0).c()
     assert lib.rr_moe_forward(C.byref(nofnn), fake, fake, None, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == INVALID
+    # misaligned data pointers: rows are moved with 16-byte vector instructions, tables with 4-byte ones
+    odd16, odd4 = C.c_void_p(0x1008), C.c_void_p(0x1002)
+    assert lib.rr_router_scores(C.byref(cc), odd16, fake, None, fake, None, None, None) == INVALID
+    assert lib.rr_router_scores(C.byref(cc), fake, odd16, None, fake, None, None, None) == INVALID
+    assert lib.rr_router_scores(C.byref(cc), fake, fake, odd4, fake, None, None, None) == INVALID
+    assert lib.rr_router_scores(C.byref(cc), fake, fake, None, odd16, None, None, None) == INVALID
+    assert lib.rr_rectified_dispatch(C.byref(cc), odd16, C.byref(tables), fake, 1 << 30, None) == INVALID
+    crooked = binding._Tables(*([0x1000] * 4 + [0x1002] + [0x1000] * 5))
+    assert lib.rr_rectified_dispatch(C.byref(cc), fake, C.byref(crooked), fake, 1 << 30, None) == INVALID
+    assert lib.rr_moe_forward(C.byref(cc), odd16, fake, None, fake, fake, fake, fake, None, None, fake, 1 << 40, None) == INVALID
+    assert lib.rr_moe_forward(C.byref(cc), fake, fake, None, fake, odd16, fake, fake, None, None, fake, 1 << 40, None) == INVALID
+    assert lib.rr_moe_forward(C.byref(cc), fake, fake, None, fake, fake, fake, odd16, None, None, fake, 1 << 40, None) == INVALID
+    assert lib.rr_router_backward(C.byref(cc), odd16, fake, None, fake, 1 << 40, 1, None, fake, None) == INVALID
+    assert lib.rr_router_backward(C.byref(cc), fake, fake, None, fake, 1 << 40, 1, None, odd4, None) == INVALID
     # backward: missing gradient buffers, unknown flag, incomplete tables, no expert outputs to read, workspace
     assert lib.rr_router_backward(C.byref(cc), None, fake, None, fake, 1 << 40, 1, None, fake, None) == INVALID
     assert lib.rr_router_backward(C.byref(cc), fake, fake, None, fake, 1 << 40, 1, None, None, None) == INVALID
