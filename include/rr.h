@@ -20,7 +20,9 @@
  *   - Matrices are dense, row-major, without padding.  int32 tables use -1 for "none".
  *   - Logits must be finite; behaviour for NaN/Inf logits is undefined.
  *   - Limits: 1 <= E <= 64, 1 <= k <= 4, T <= 2^24, d_model % 8 == 0, d_ff % 8 == 0, and with
- *     RR_QUOTA_PER_GROUP (T/G) % 128 == 0; outside them calls return RR_ERR_UNSUPPORTED.
+ *     RR_QUOTA_PER_GROUP (T/G) % 128 == 0; with bf16 expert FFNs, (C + T) * max(d_model, d_ff) and
+ *     d_model * d_ff below 2^30 elements (one expert's rows and one weight matrix are addressed with
+ *     32-bit byte offsets); outside them calls return RR_ERR_UNSUPPORTED.
  */
 #ifndef RR_H
 #define RR_H

@@ -90,6 +90,14 @@ static int make_dims(const rr_config *c, bool need_ffn, Dims *D) {
   int64_t rmax = (slots < assigns ? slots : assigns) + (D->ir ? c->T : 0);
   if (rmax > ((int64_t)1 << 28)) return RR_ERR_UNSUPPORTED;
   D->Rmax = (int)rmax;
+  if (need_ffn && c->dtype == RR_BF16) {
+    // the grouped GEMM addresses one expert's rows, and one expert's weight matrix, with 32-bit byte offsets
+    int64_t rows_max = (int64_t)C + (D->ir ? c->T : 0);
+    if (rows_max > rmax) rows_max = rmax;
+    const int64_t kmax = c->d_model > c->d_ff ? c->d_model : c->d_ff;
+    if (rows_max * kmax * 2 >= ((int64_t)1 << 31) || (int64_t)c->d_model * c->d_ff * 2 >= ((int64_t)1 << 31))
+      return RR_ERR_UNSUPPORTED;
+  }
   D->BM = c->dtype == RR_BF16 ? 256 : 64;
   D->max_mtiles = need_ffn ? D->Rmax / D->BM + c->E : 0;  // routing-only calls cut no GEMM row tiles
   return RR_OK;

@@ -97,6 +97,9 @@ def _ws_status(lib, cfg):
     (dict(E=128, G=2), UNSUPPORTED), (dict(k=5, E=8), UNSUPPORTED), (dict(dtype=7), UNSUPPORTED),
     (dict(d_model=60), UNSUPPORTED), (dict(d_ff=100), UNSUPPORTED), (dict(act=5), UNSUPPORTED),
     (dict(T=1 << 25, G=2), UNSUPPORTED),
+    # bf16 FFN: one expert's rows (up to C + T) or one weight matrix past 32-bit byte offsets
+    (dict(T=1 << 20, d_model=1024, d_ff=4096, E=64, G=8), UNSUPPORTED), (dict(d_model=32768, d_ff=32768), UNSUPPORTED),
+    (dict(T=1 << 17, d_model=1024, d_ff=4096, E=64, G=8), RR_OK),
     (dict(flags=rr.RR_QUOTA_PER_GROUP | rr.RR_INTRA_GPU | rr.RR_FILL_IN), RR_OK),   # 512 tokens per group
     (dict(flags=rr.RR_QUOTA_PER_GROUP, T=1000), UNSUPPORTED),                      # groups must hold whole token blocks
     (dict(flags=rr.RR_QUOTA_PER_GROUP, T=1024, G=8, E=8), RR_OK),
