@@ -12,7 +12,16 @@
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates no
- *     device memory and keeps no data between calls; scratch comes from `workspace`.
+ *     device memory and keeps no DATA between calls; scratch comes from `workspace`.
+ *     Process state it does keep: per device, whether rr_init has run (kernel attributes) - set
+ *     once, thread-safe - and the record of the benchmarking profiler (rr_profile_*, one thread
+ *     only).
+ *   - Thread safety: calls from several host threads are safe as long as they do not share a
+ *     workspace or output buffers (and do not use the profiler).
+ *   - Graph capture: every call only enqueues kernels on `stream` (no allocation, no memset, no
+ *     synchronisation) and may be captured in a HIP graph, provided rr_init() has run on that
+ *     device before the capture starts (the first call on a device otherwise runs it itself,
+ *     which is host-side set-up that does not belong in a capture).
  *   - `stream` is a hipStream_t (NULL = the null stream).  Calls enqueue work and return
  *     without waiting for it.
  *   - Return value: RR_OK (0) or a negative rr_status; rr_strerror() names it.  Arguments are
@@ -100,6 +109,12 @@ typedef struct rr_tables {
 /* Alignment: x, the expert weights, out, dout, w_router, logits and probs must be 16-byte aligned
  * (rows are moved with 16-byte vector instructions), every other array 4-byte aligned, the workspace
  * 256-byte aligned; a misaligned pointer is RR_ERR_INVALID_ARG (workspace: RR_ERR_WORKSPACE). */
+
+/* One-time, per-device host-side set-up for the current device: raises the dynamic-LDS limit of the
+ * grouped-GEMM kernels.  Idempotent and
+ * thread-safe.  Every entry point runs it on its first call on a device; call it explicitly before
+ * capturing calls in a HIP graph.  Returns RR_OK or RR_ERR_HIP. */
+int rr_init(void);
 
 /* Sec. 3: capacity = capacity factor x tokens / experts, rounded up, at least 1.
  * Evaluated as ceil((double)cf * T / E).  Host function; returns -1 on invalid arguments. */

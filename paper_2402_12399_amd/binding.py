@@ -86,6 +86,8 @@ def load_library():
     lib.rr_moe_forward.argtypes = [C.POINTER(_Config), vp, vp, vp, vp, vp, vp, vp, C.POINTER(_Tables), vp, vp, sz, vp]
     lib.rr_router_backward.restype = C.c_int
     lib.rr_router_backward.argtypes = [C.POINTER(_Config), vp, vp, C.POINTER(_Tables), vp, sz, C.c_uint32, vp, vp, vp]
+    lib.rr_init.restype = C.c_int
+    lib.rr_init.argtypes = []
     lib.rr_profile_enable.restype = C.c_int
     lib.rr_profile_enable.argtypes = [C.c_int]
     lib.rr_profile_read.restype = C.c_int
@@ -112,6 +114,10 @@ def _ptr(t):
 def _stream():
     import torch
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def rr_init():
+    _check(load_library().rr_init(), "rr_init")
 
 
 def rr_capacity(T: int, E: int, capacity_factor: float) -> int:

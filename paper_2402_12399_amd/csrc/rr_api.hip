@@ -2,11 +2,27 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
 #include <vector>
 
 #include "rr_internal.h"
 
 namespace rr {
+
+// ------------------------------------------------------------------ per-device set-up
+constexpr int kMaxDevices = 64;
+static std::once_flag g_dev_once[kMaxDevices];
+static hipError_t g_dev_status[kMaxDevices];
+
+// Runs once per device, with that device current.  Returns the device index, or -1.
+static int device_setup() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
+  std::call_once(g_dev_once[dev], [dev] {
+    g_dev_status[dev] = ffn_kernel_attributes();
+  });
+  return g_dev_status[dev] == hipSuccess ? dev : -1;
+}
 
 // ------------------------------------------------------------------ profiling record
 struct ProfSpan { int id; hipEvent_t a, b; };
@@ -221,6 +237,8 @@ int rr_router_scores(const rr_config *cfg, const void *x, const float *w_router,
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
 }
 
+int rr_init(void) { return device_setup() >= 0 ? RR_OK : RR_ERR_HIP; }
+
 int rr_rectified_dispatch(const rr_config *cfg, const float *logits, const rr_tables *out, void *workspace,
                           size_t workspace_bytes, void *stream) {
   Dims D;
@@ -258,6 +276,7 @@ int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, c
   memset(&W, 0, sizeof(W));
   rc = check_ws(D, !routing_only, workspace, workspace_bytes, &W);
   if (rc != RR_OK) return rc;
+  if (!routing_only && device_setup() < 0) return RR_ERR_HIP;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const rr_tables &tb = tables ? *tables : W.tables;
   float *lg = logits ? logits : W.logits;

@@ -722,19 +722,36 @@ hipError_t set_lds(Kern kern, int bytes) {
 }
 
 int cu_count() {
-  static int n = 0;
-  if (n == 0) {
-    int dev = 0;
+  static const int n = [] {  // initialised once, thread-safe (C++11 static)
+    int dev = 0, cus = 0;
     hipDeviceProp_t prop;
-    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) n = prop.multiProcessorCount;
-    if (n <= 0) n = 256;
-  }
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess) cus = prop.multiProcessorCount;
+    return cus > 0 ? cus : 256;
+  }();
   return n;
 }
 
 bool persistent_ok(int K) { return K % GB_BK == 0 && K >= 3 * GB_BK; }  // whole K chunks, at least three
 
 }  // namespace
+
+// The bf16 kernels use more dynamic LDS than the default limit.  Raising it is host-side set-up of the
+// loaded code object on the current device (no stream work); the caller runs it once per device.
+hipError_t ffn_kernel_attributes() {
+  hipError_t e = hipSuccess;
+  auto set = [&e](auto kern, int bytes) {
+    if (e == hipSuccess) e = set_lds(kern, bytes);
+  };
+  set(gemm_bf16_persistent_kernel<true, -1, true>, PK_SMEM);
+  set(gemm_bf16_persistent_kernel<true, -1, false>, PK_SMEM);
+  set(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, true>, PK_SMEM);
+  set(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, false>, PK_SMEM);
+  set(gemm_bf16_persistent_kernel<false, -1, false>, PK_SMEM);
+  set(gemm_bf16_staged_kernel<true, -1>, PK_LDS);
+  set(gemm_bf16_staged_kernel<false, RR_ACT_GELU>, PK_LDS);
+  set(gemm_bf16_staged_kernel<false, -1>, PK_LDS);
+  return e;
+}
 
 bool ffn_fuses_gather(const Dims &D) {
   return D.dtype == RR_BF16 && persistent_ok(D.d) && (long long)D.T * D.d * 2 < 0x7ffffff0ll;
@@ -747,21 +764,8 @@ hipError_t launch_ffn_part(const Dims &D, const void *x, const rr_tables &tb, co
   GemmArgs up{fuse ? x : W.x_disp, w1, w3, W.h, D.d, D.F, 0, W.tiles, W.tile_ctl,
               tb.slot_token, tb.ir_token, D.quota ? W.row_token : nullptr, D.C, (long long)D.T * D.d * 2};
   GemmArgs down{W.h, w2, nullptr, W.y, D.F, D.d, 0, W.tiles, W.tile_ctl, nullptr, nullptr, nullptr, 0, 0};
-  hipError_t err = hipSuccess;
   if (D.dtype == RR_BF16) {
     const bool gated = D.act == RR_ACT_SWIGLU;
-    static bool attr_done = false;
-    if (!attr_done) {
-      if ((err = set_lds(gemm_bf16_persistent_kernel<true, -1, true>, PK_SMEM)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_persistent_kernel<true, -1, false>, PK_SMEM)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, true>, PK_SMEM)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, false>, PK_SMEM)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_persistent_kernel<false, -1, false>, PK_SMEM)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_staged_kernel<true, -1>, PK_LDS)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_staged_kernel<false, RR_ACT_GELU>, PK_LDS)) != hipSuccess) return err;
-      if ((err = set_lds(gemm_bf16_staged_kernel<false, -1>, PK_LDS)) != hipSuccess) return err;
-      attr_done = true;
-    }
     up.NT = gated ? (D.F + 127) / 128 : (D.F + 255) / 256;
     down.NT = (D.d + 255) / 256;
     const int cus = cu_count();

@@ -28,7 +28,7 @@ def test_every_declared_function_is_exported(lib):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(rr_[a-z_]+)\s*\(", header))
     assert {"rr_capacity", "rr_slots_per_expert", "rr_workspace_bytes", "rr_router_scores", "rr_rectified_dispatch", "rr_moe_forward", "rr_router_backward",
-            "rr_profile_enable", "rr_profile_read", "rr_strerror"} <= declared
+            "rr_init", "rr_profile_enable", "rr_profile_read", "rr_strerror"} <= declared
     for name in declared:
         assert hasattr(lib, name), f"{name} declared in rr.h but not exported by librr.so"
 
