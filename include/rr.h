@@ -12,12 +12,13 @@
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer owned by the caller.  The library allocates no
- *     device memory and keeps no DATA between calls; scratch comes from `workspace`.
- *     Process state it does keep: per device, whether rr_init has run (kernel attributes) - set
- *     once, thread-safe - and the record of the benchmarking profiler (rr_profile_*, one thread
- *     only).
+ *     device memory and keeps no DATA between calls; scratch comes from `workspace` (one entry
+ *     point, rr_rectified_dispatch_static, uses a fixed buffer inside the library instead).
+ *     Process state it does keep: per device, whether rr_init has run (kernel attributes, the
+ *     address of the static scratch buffer) - set once, thread-safe - and the record of the
+ *     benchmarking profiler (rr_profile_*, one thread only).
  *   - Thread safety: calls from several host threads are safe as long as they do not share a
- *     workspace or output buffers (and do not use the profiler).
+ *     workspace or output buffers (and do not use the profiler or the static scratch buffer).
  *   - Graph capture: every call only enqueues kernels on `stream` (no allocation, no memset, no
  *     synchronisation) and may be captured in a HIP graph, provided rr_init() has run on that
  *     device before the capture starts (the first call on a device otherwise runs it itself,
@@ -48,7 +49,9 @@ typedef enum rr_status {
   RR_ERR_INVALID_ARG = -1, /* NULL pointer, non-positive size, E % G, T % G, k > E, Fill-in with k+1 > E */
   RR_ERR_UNSUPPORTED = -2, /* dtype / activation / size outside the limits above */
   RR_ERR_WORKSPACE   = -3, /* workspace NULL, misaligned (256 B) or smaller than rr_workspace_bytes */
-  RR_ERR_HIP         = -4  /* a HIP call or kernel launch failed */
+  RR_ERR_HIP         = -4, /* a HIP call or kernel launch failed */
+  RR_ERR_TOO_LARGE   = -5  /* rr_rectified_dispatch_static: the configuration needs more scratch than
+                              RR_STATIC_WORKSPACE_BYTES */
 } rr_status;
 
 enum { RR_F32 = 0, RR_BF16 = 1 };             /* rr_config.dtype */
@@ -111,7 +114,7 @@ typedef struct rr_tables {
  * 256-byte aligned; a misaligned pointer is RR_ERR_INVALID_ARG (workspace: RR_ERR_WORKSPACE). */
 
 /* One-time, per-device host-side set-up for the current device: raises the dynamic-LDS limit of the
- * grouped-GEMM kernels.  Idempotent and
+ * grouped-GEMM kernels and looks up the address of the static scratch buffer.  Idempotent and
  * thread-safe.  Every entry point runs it on its first call on a device; call it explicitly before
  * capturing calls in a HIP graph.  Returns RR_OK or RR_ERR_HIP. */
 int rr_init(void);
@@ -145,6 +148,19 @@ int rr_router_scores(const rr_config *cfg, const void *x, const float *w_router,
  * integer tables are a deterministic function of the logits. */
 int rr_rectified_dispatch(const rr_config *cfg, const float *logits, const rr_tables *out,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/* rr_rectified_dispatch for callers that cannot allocate device memory or size a workspace - code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same inputs,
+ * outputs and results; the scratch is a buffer of RR_STATIC_WORKSPACE_BYTES that lives in the
+ * library's device image (one copy per GPU the library runs on, held until the process ends).  The
+ * call allocates nothing.  A configuration whose rr_workspace_bytes (with d_ff = 0) exceeds
+ * RR_STATIC_WORKSPACE_BYTES is refused with RR_ERR_TOO_LARGE before anything is launched (at
+ * k = 2 with Fill-in and 64 experts that is about 600 K tokens).  All calls on one GPU share
+ * that GPU's buffer: calls that overlap on one GPU - two streams, two host threads - race; issue
+ * them on one stream.  Nothing in the buffer needs to start at zero (every kernel writes what the
+ * next one reads), so the contents left by an earlier call do not matter. */
+#define RR_STATIC_WORKSPACE_BYTES (32u << 20)
+int rr_rectified_dispatch_static(const rr_config *cfg, const float *logits, const rr_tables *out, void *stream);
 
 /* The whole layer: router -> slotting -> rectifications -> dispatch gather -> per-expert FFN
  * (grouped GEMM) -> weighted combine (Eq. 2 / Eq. 3).

@@ -82,6 +82,8 @@ def load_library():
     lib.rr_router_scores.argtypes = [C.POINTER(_Config), vp, vp, vp, vp, vp, vp, vp]
     lib.rr_rectified_dispatch.restype = C.c_int
     lib.rr_rectified_dispatch.argtypes = [C.POINTER(_Config), vp, C.POINTER(_Tables), vp, sz, vp]
+    lib.rr_rectified_dispatch_static.restype = C.c_int
+    lib.rr_rectified_dispatch_static.argtypes = [C.POINTER(_Config), vp, C.POINTER(_Tables), vp]
     lib.rr_moe_forward.restype = C.c_int
     lib.rr_moe_forward.argtypes = [C.POINTER(_Config), vp, vp, vp, vp, vp, vp, vp, C.POINTER(_Tables), vp, vp, sz, vp]
     lib.rr_router_backward.restype = C.c_int
@@ -186,6 +188,13 @@ def rr_rectified_dispatch(cfg: RRConfig, logits, tables: Tables, workspace):
     cc, tc = cfg.c(), tables.c()
     _check(load_library().rr_rectified_dispatch(C.byref(cc), _ptr(logits), C.byref(tc), _ptr(workspace),
                                                 workspace.numel(), _stream()), "rr_rectified_dispatch")
+
+
+def rr_rectified_dispatch_static(cfg: RRConfig, logits, tables: Tables):
+    """rr_rectified_dispatch with the library's own static scratch buffer (allocates nothing)."""
+    cc, tc = cfg.c(), tables.c()
+    _check(load_library().rr_rectified_dispatch_static(C.byref(cc), _ptr(logits), C.byref(tc), _stream()),
+           "rr_rectified_dispatch_static")
 
 
 def rr_moe_forward(cfg: RRConfig, x, w_router, bias, w1, w3, w2, out, tables: Tables | None, logits, workspace):

@@ -7,19 +7,28 @@
 
 #include "rr_internal.h"
 
+// Scratch of rr_rectified_dispatch_static.  In host code this name is only a handle for
+// hipGetSymbolAddress; the device address, one per GPU, is looked up once per device (device_setup).
+static __device__ __align__(256) unsigned char scratch[RR_STATIC_WORKSPACE_BYTES];
+
 namespace rr {
 
 // ------------------------------------------------------------------ per-device set-up
 constexpr int kMaxDevices = 64;
 static std::once_flag g_dev_once[kMaxDevices];
 static hipError_t g_dev_status[kMaxDevices];
+static void *g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU
 
 // Runs once per device, with that device current.  Returns the device index, or -1.
 static int device_setup() {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
   std::call_once(g_dev_once[dev], [dev] {
-    g_dev_status[dev] = ffn_kernel_attributes();
+    hipError_t e = ffn_kernel_attributes();
+    void *p = nullptr;
+    if (e == hipSuccess) e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    g_scratch_ptr[dev] = e == hipSuccess ? p : nullptr;
+    g_dev_status[dev] = e;
   });
   return g_dev_status[dev] == hipSuccess ? dev : -1;
 }
@@ -239,6 +248,23 @@ int rr_router_scores(const rr_config *cfg, const void *x, const float *w_router,
 
 int rr_init(void) { return device_setup() >= 0 ? RR_OK : RR_ERR_HIP; }
 
+int rr_rectified_dispatch_static(const rr_config *cfg, const float *logits, const rr_tables *out, void *stream) {
+  Dims D;
+  int rc = make_dims(cfg, false, &D);
+  if (rc != RR_OK) return rc;
+  if (!logits || !tables_complete(out)) return RR_ERR_INVALID_ARG;
+  if (!aligned16(logits) || !tables_aligned(out)) return RR_ERR_INVALID_ARG;
+  Work probe;
+  if (carve(D, false, nullptr, &probe) > (size_t)RR_STATIC_WORKSPACE_BYTES) return RR_ERR_TOO_LARGE;
+  const int dev = device_setup();
+  if (dev < 0 || !g_scratch_ptr[dev]) return RR_ERR_HIP;
+  Work W;
+  memset(&W, 0, sizeof(W));
+  carve(D, false, g_scratch_ptr[dev], &W);
+  hipError_t e = launch_dispatch(D, logits, *out, W, false, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? RR_OK : RR_ERR_HIP;
+}
+
 int rr_rectified_dispatch(const rr_config *cfg, const float *logits, const rr_tables *out, void *workspace,
                           size_t workspace_bytes, void *stream) {
   Dims D;
@@ -343,6 +369,7 @@ const char *rr_strerror(int code) {
     case RR_ERR_UNSUPPORTED: return "unsupported configuration";
     case RR_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case RR_ERR_HIP: return "HIP runtime or launch failure";
+    case RR_ERR_TOO_LARGE: return "configuration needs more scratch than the library's static buffer (RR_STATIC_WORKSPACE_BYTES)";
     default: return "unknown rr_status";
   }
 }
