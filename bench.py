@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c5")
     ap.add_argument("--mode", default="ir+fr", help="vanilla | ir | fr | ir+fr")
+    ap.add_argument("--bias", default=None,
+                    help="override the workload's router bias recipe: none | normal:<std> | zipf:<s> (load balance study)")
     ap.add_argument("--quota", action="store_true",
                     help="capacity per group (RR_QUOTA_PER_GROUP) instead of one queue per expert over all tokens")
     ap.add_argument("--cpu-sample", type=int, default=1024, help="tokens the CPU oracle computes outputs for (0 = skip)")
@@ -320,6 +322,9 @@ def main():
         return 0
 
     w = wl.ALL[args.workload]
+    if args.bias is not None:
+        import dataclasses
+        w = dataclasses.replace(w, name=w.name + "_bias_" + args.bias, bias=args.bias)
     if w.d_ff == 0:  # the routing-only workload on its own
         torch.cuda.set_device(0)
         st = routing_stress(rr, wl, torch, args.steps, args.warmup)

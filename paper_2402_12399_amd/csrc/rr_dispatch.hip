@@ -187,7 +187,8 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
                                                                        const int32_t *__restrict__ blk_off,
                                                                        const int32_t *__restrict__ cat_cnt,
                                                                        u32 *__restrict__ cand_key,
-                                                                       int32_t *__restrict__ cand_tok) {
+                                                                       int32_t *__restrict__ cand_tok,
+                                                                       int32_t *__restrict__ slot) {
   constexpr int NW = kTokBlock / kWave;
   __shared__ int wcnt[kMaxRounds][NW][kMaxE];
   __shared__ int s_base[kMaxRounds * kMaxE];
@@ -244,6 +245,9 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
       for (int q = 0; q < w; ++q) pos += wcnt[r][q][e];
       cand_key[pos] = key_r[r];
       cand_tok[pos] = i;
+      // "dropped" until select_slot says otherwise: written here, token by token (whole cache lines),
+      // so that the list-major selection only has to touch the entries of the tokens it keeps
+      slot[(size_t)i * (A.k + 1) + r] = -1;
     }
   }
 }
@@ -252,23 +256,43 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
 constexpr int SS_THREADS = 1024;
 constexpr int SS_WAVES = SS_THREADS / kWave;
 constexpr int SS_PER = 24;  // keys a thread keeps in registers: lists up to 24576 candidates take the register path
+constexpr int kHistCopies = 32;  // counters per histogram bin (see radix_select)
+constexpr int kHistWords = 256 * (1 + kHistCopies);
 
 // m-th largest key among those that `each` enumerates, by 8-bit digits from the top (Sec. 3: the
 // lowest scores are dropped).  Returns the threshold key; need_eq = how many of the keys equal to it
-// are kept (the first ones in token order).  `each(f)` calls f(key) for every key of the calling
-// thread; all threads of the workgroup call this together.
+// are kept (the first ones in token order).  `each(f)` calls f(key, valid) for every key slot of the
+// calling thread, the same number of times in every lane of a wave (invalid slots with valid = false);
+// all threads of the workgroup call this together.
+// Scores of one list share their leading digits, so most lanes of a wave hit the same histogram
+// bin, and LDS atomics of one instruction on one address are served one lane after the other: every
+// bin has kHistCopies counters, lane l adds to copy l % kHistCopies (consecutive words, different
+// banks), and the copies are added up before the bins are scanned.
 template <class Each>
 __device__ inline u32 radix_select(int m, Each each, u32 *hist, u32 *s_pick, u32 &need_eq) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  u32 *copies = hist + 256;  // [256][kHistCopies]
   u32 prefix = 0, remaining = (u32)m;
   for (int pass = 3; pass >= 0; --pass) {
     const int shift = pass * 8;
-    if (tid < 256) hist[tid] = 0;
+#pragma unroll
+    for (int q = 0; q < 256 * kHistCopies / SS_THREADS; ++q) copies[q * SS_THREADS + tid] = 0;
     __syncthreads();
-    each([&](u32 kx) {
-      const bool match = pass == 3 || ((kx ^ prefix) >> (shift + 8)) == 0;
-      if (match) atomicAdd(&hist[(kx >> shift) & 255u], 1u);
+    each([&](u32 kx, bool valid) {
+      if (valid && (pass == 3 || ((kx ^ prefix) >> (shift + 8)) == 0))
+        atomicAdd(&copies[((kx >> shift) & 255u) * kHistCopies + (lane & (kHistCopies - 1))], 1u);
     });
+    __syncthreads();
+    {  // thread t adds up a quarter of the copies of bin t / 4
+      static_assert(SS_THREADS == 4 * 256 && kHistCopies % 4 == 0, "four threads per bin");
+      const u32 *c = copies + (tid >> 2) * kHistCopies + (tid & 3) * (kHistCopies / 4);
+      u32 sum = 0;
+#pragma unroll
+      for (int q = 0; q < kHistCopies / 4; ++q) sum += c[q];
+      sum += __shfl_xor(sum, 1);
+      sum += __shfl_xor(sum, 2);
+      if ((tid & 3) == 0) hist[tid >> 2] = sum;
+    }
     __syncthreads();
     if (w == 0) {
       // lane l owns bins 255-4l .. 252-4l, i.e. bins in descending order across lanes
@@ -316,7 +340,7 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
                                                                  int32_t *__restrict__ grp_off,
                                                                  int32_t *__restrict__ fill_topk,
                                                                  int32_t *__restrict__ fill_total) {
-  __shared__ u32 hist[256];
+  __shared__ u32 hist[kHistWords];
   __shared__ u32 s_pick[2];
   __shared__ int2 wtot[SS_PER][SS_WAVES];  // (kept-for-sure, equal-to-threshold) counts per (trip, wave)
   __shared__ int2 wsum[8];
@@ -397,7 +421,7 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
       thr = radix_select(m, [&](auto f) {
 #pragma unroll
         for (int u = 0; u < SS_PER; ++u)
-          if (u < nu && u * SS_THREADS + tid < n) f(kreg[u]);
+          if (u < nu) f(kreg[u], u * SS_THREADS + tid < n);
       }, hist, s_pick, need_eq);
 
     int pre[SS_PER];  // lanes of this wave before this one: kept-for-sure | equal << 8
@@ -445,14 +469,19 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
         const int eqs = base.y + ((pre[u] >> 8) & 255);  // equal keys before this one
         const bool kept = gt || (eq && (u32)eqs < need_eq);
         const int sl = fill0 + base.x + (pre[u] & 255) + min(eqs, (int)need_eq);
-        slot[(size_t)treg[u] * (A.k + 1) + r] = kept ? sl : -1;
-        if (kept) slot_token[(size_t)j * A.C + sl] = treg[u];
+        if (kept) {
+          slot[(size_t)treg[u] * (A.k + 1) + r] = sl;
+          slot_token[(size_t)j * A.C + sl] = treg[u];
+        }
       }
     }
   } else {
     if (mode == 3)
       thr = radix_select(m, [&](auto f) {
-        for (int idx = tid; idx < n; idx += SS_THREADS) f(keys[idx]);
+        for (int base = 0; base < n; base += SS_THREADS) {
+          const int idx = base + tid;
+          f(idx < n ? keys[idx] : 0u, idx < n);
+        }
       }, hist, s_pick, need_eq);
     int run_gt = 0, run_eq = 0;
     for (int base = 0; base < n; base += SS_THREADS) {
@@ -481,8 +510,10 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
         bool kept = gt || (eq && (u32)eqs < need_eq);
         int kept_before = run_gt + gt_before + min(eqs, (int)need_eq);
         int sl = fill0 + kept_before;
-        slot[(size_t)tok * (A.k + 1) + r] = kept ? sl : -1;
-        if (kept) slot_token[(size_t)j * A.C + sl] = tok;
+        if (kept) {
+          slot[(size_t)tok * (A.k + 1) + r] = sl;
+          slot_token[(size_t)j * A.C + sl] = tok;
+        }
       }
       run_gt += tot_gt;
       run_eq += tot_eq;
@@ -510,7 +541,7 @@ __global__ __launch_bounds__(SS_THREADS) void select_direct_kernel(DispatchArgs 
                                                                    int32_t *__restrict__ grp_off,
                                                                    int32_t *__restrict__ fill_topk,
                                                                    int32_t *__restrict__ fill_total) {
-  __shared__ u32 hist[256];
+  __shared__ u32 hist[kHistWords];
   __shared__ u32 s_pick[2];
   __shared__ int2 wtot[SS_PER][SS_WAVES];
   __shared__ int2 wsum[8];
@@ -572,7 +603,7 @@ __global__ __launch_bounds__(SS_THREADS) void select_direct_kernel(DispatchArgs 
     thr = radix_select(m, [&](auto f) {
 #pragma unroll
       for (int u = 0; u < SS_PER; ++u)
-        if ((member >> u) & 1u) f(kreg[u]);
+        if (u < nu) f(kreg[u], (member >> u) & 1u);
     }, hist, s_pick, need_eq);
   if (mode == 2) need_eq = (u32)m;  // arrival order: every candidate "ties", the first m of them are kept
 
@@ -641,7 +672,8 @@ __global__ __launch_bounds__(kTokBlock) void ir_count_kernel(DispatchArgs A, con
                                                              const int32_t *__restrict__ ir_cand,
                                                              int32_t *__restrict__ ir_blk_cnt) {
   __shared__ int cnt[kMaxE];
-  const int tid = threadIdx.x, b = blockIdx.x;
+  // neighbouring blocks write neighbouring words of the per-expert count rows: XCD-aware block order
+  const int tid = threadIdx.x, b = xcd_block(blockIdx.x, A.NB);
   const int i = b * kTokBlock + tid;
   if (tid < kMaxE) cnt[tid] = 0;
   __syncthreads();
@@ -845,7 +877,7 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     prof_end(K_SCAN_CAND, s);
     prof_begin(K_SCATTER_CAND, s);
     scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_cnt, W.cand_key,
-                                                         W.cand_tok);
+                                                         W.cand_tok, tb.slot);
     prof_end(K_SCATTER_CAND, s);
     prof_begin(K_SELECT_SLOT, s);
     select_slot_kernel<<<D.NL, SS_THREADS, 0, s>>>(A, W.cat_cnt, W.blk_cnt, W.cand_key, W.cand_tok, tb.slot,
