@@ -152,6 +152,11 @@ static size_t carve(const Dims &D, bool forward, void *ws, Work *W) {
   W->row_token = D.quota ? cv.take<int32_t>(D.Rmax) : nullptr;
   W->cand_key = cv.take<u32>(T * NR);
   W->cand_tok = cv.take<int32_t>(T * NR);
+  const bool splits = select_splits(D.T, D.NR, D.NL);
+  W->comp_key = splits ? cv.take<u32>(T * NR) : nullptr;
+  W->comp_tok = splits ? cv.take<int32_t>(T * NR) : nullptr;
+  W->seg_cnt = splits ? cv.take<int32_t>(D.NL + T * NR / kSelectSegLen + 1) : nullptr;
+  W->list_done = splits ? cv.take<int32_t>(D.NL) : nullptr;
   W->ir_blk_cnt = cv.take<int32_t>(E * D.NB);
   W->ir_cnt = cv.take<int32_t>(E);
   W->row_base = cv.take<int32_t>(E + 1);

@@ -126,9 +126,12 @@ __global__ __launch_bounds__(kTokBlock) void topk_rank_kernel(const float *__res
 // One workgroup per list: exclusive scan of a[list][0..NB) in place, total to tot[list].  A thread
 // scans SC_PER consecutive entries in registers, so 8192 entries are one trip with two barriers.
 constexpr int SC_THREADS = 1024, SC_PER = 8, SC_WAVES = SC_THREADS / kWave;
+// zero: nullptr, or an array of which every workgroup clears nzero entries from blockIdx.x * nzero on.
 __global__ __launch_bounds__(SC_THREADS) void scan_blocks_kernel(int32_t *__restrict__ a, int32_t *__restrict__ tot,
-                                                                 int NB) {
+                                                                 int NB, int32_t *__restrict__ zero, int nzero) {
   __shared__ int wsum[SC_WAVES];
+  if (zero)
+    for (int q = threadIdx.x; q < nzero; q += SC_THREADS) zero[(size_t)blockIdx.x * nzero + q] = 0;
   int32_t *p = a + (size_t)blockIdx.x * NB;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const bool vec = (NB & 3) == 0;  // then every list starts 16-byte aligned
@@ -255,7 +258,7 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
 // ------------------------------------------------------------------ select_slot
 constexpr int SS_THREADS = 1024;
 constexpr int SS_WAVES = SS_THREADS / kWave;
-constexpr int SS_PER = 24;  // keys a thread keeps in registers: lists up to 24576 candidates take the register path
+constexpr int SS_PER = kSelectRegMax / SS_THREADS;  // keys a thread keeps in registers (24)
 constexpr int kHistCopies = 32;  // counters per histogram bin (see radix_select)
 constexpr int kHistWords = 256 * (1 + kHistCopies);
 
@@ -322,6 +325,147 @@ __device__ inline u32 radix_select(int m, Each each, u32 *hist, u32 *s_pick, u32
   return prefix;
 }
 
+// Shared memory of the selection kernels.
+struct SelectSmem {
+  u32 hist[kHistWords];
+  u32 pick[2];
+  int2 wtot[SS_PER][SS_WAVES];  // (kept-for-sure, equal-to-threshold) counts per (trip, wave)
+  int2 wsum[8];
+};
+
+// Selection and slotting of a list of n <= SS_THREADS * SS_PER candidates held in registers: candidate
+// idx = u * SS_THREADS + tid is element u of thread tid (`load(idx, key, tok)` fetches it), so the
+// candidates are met in token order.  by_score: the m highest keys are kept, equal keys in token order
+// (radix select of the threshold, four digit passes on registers); otherwise the first m in token
+// order.  Kept candidates take slots fill0, fill0 + 1, ... in token order: one scan over the
+// (trip, wave) totals of the kept flags.  Only kept candidates are written (every slot entry starts
+// as -1).
+template <class Load>
+__device__ inline void select_in_registers(const DispatchArgs &A, int n, int m, bool by_score, int r, int j, int fill0,
+                                           Load load, SelectSmem &S, int32_t *__restrict__ slot,
+                                           int32_t *__restrict__ slot_token) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  const int nu = (n + SS_THREADS - 1) / SS_THREADS;
+  u32 kreg[SS_PER];
+  int treg[SS_PER];
+#pragma unroll
+  for (int u = 0; u < SS_PER; ++u) {
+    const int idx = u * SS_THREADS + tid;
+    kreg[u] = 0;
+    treg[u] = 0;
+    if (u < nu && idx < n) load(idx, kreg[u], treg[u]);
+  }
+  u32 thr = 0, need_eq = 0;
+  if (by_score)
+    thr = radix_select(m, [&](auto f) {
+#pragma unroll
+      for (int u = 0; u < SS_PER; ++u)
+        if (u < nu) f(kreg[u], u * SS_THREADS + tid < n);
+    }, S.hist, S.pick, need_eq);
+
+  int pre[SS_PER];  // lanes of this wave before this one: kept-for-sure | equal << 8
+#pragma unroll
+  for (int u = 0; u < SS_PER; ++u) {
+    pre[u] = 0;
+    if (u < nu) {
+      const int idx = u * SS_THREADS + tid;
+      const bool valid = idx < n;
+      bool gt, eq = false;
+      if (by_score) { gt = valid && kreg[u] > thr; eq = valid && kreg[u] == thr; }
+      else gt = valid && idx < m;
+      const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+      pre[u] = __popcll(bgt & below) | (__popcll(beq & below) << 8) | (gt ? 1 << 16 : 0) | (eq ? 1 << 17 : 0);
+      if (lane == 0) S.wtot[u][w] = make_int2(__popcll(bgt), __popcll(beq));
+    }
+  }
+  __syncthreads();
+  // exclusive scan of the nu * SS_WAVES totals in (trip, wave) order = token order
+  const int ne = nu * SS_WAVES;
+  int2 mine = make_int2(0, 0), incl = mine;
+  if (tid < ne) mine = (&S.wtot[0][0])[tid];
+  if (tid < 8 * kWave) {  // SS_PER * SS_WAVES = 384 entries fit 6 waves
+    incl = mine;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int tx = __shfl_up(incl.x, off), ty = __shfl_up(incl.y, off);
+      if (lane >= off) { incl.x += tx; incl.y += ty; }
+    }
+    if (lane == 63) S.wsum[w] = incl;
+  }
+  __syncthreads();
+  if (tid < ne) {
+    int2 before = make_int2(0, 0);
+    for (int q = 0; q < w; ++q) { before.x += S.wsum[q].x; before.y += S.wsum[q].y; }
+    (&S.wtot[0][0])[tid] = make_int2(before.x + incl.x - mine.x, before.y + incl.y - mine.y);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int u = 0; u < SS_PER; ++u) {
+    if (u < nu && u * SS_THREADS + tid < n) {
+      const int2 base = S.wtot[u][w];
+      const bool gt = (pre[u] >> 16) & 1, eq = (pre[u] >> 17) & 1;
+      const int eqs = base.y + ((pre[u] >> 8) & 255);  // equal keys before this one
+      if (gt || (eq && (u32)eqs < need_eq)) {
+        const int sl = fill0 + base.x + (pre[u] & 255) + min(eqs, (int)need_eq);
+        slot[(size_t)treg[u] * (A.k + 1) + r] = sl;
+        slot_token[(size_t)j * A.C + sl] = treg[u];
+      }
+    }
+  }
+}
+
+// The same for a list of any length, streamed from memory by one workgroup: the threshold by four
+// digit passes over the keys, then a pass that hands out the slots 1024 candidates at a time.  The
+// path for lists that fit neither the registers nor the split scheme below; exact for any input.
+__device__ inline void select_streaming(const DispatchArgs &A, int n, int m, bool by_score, int r, int j, int fill0,
+                                        const u32 *__restrict__ keys, const int32_t *__restrict__ toks, SelectSmem &S,
+                                        int32_t *__restrict__ slot, int32_t *__restrict__ slot_token) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  u32 thr = 0, need_eq = 0;
+  if (by_score)
+    thr = radix_select(m, [&](auto f) {
+      for (int base = 0; base < n; base += SS_THREADS) {
+        const int idx = base + tid;
+        f(idx < n ? keys[idx] : 0u, idx < n);
+      }
+    }, S.hist, S.pick, need_eq);
+  int run_gt = 0, run_eq = 0;
+  for (int base = 0; base < n; base += SS_THREADS) {
+    const int idx = base + tid;
+    const bool valid = idx < n;
+    u32 kx = 0;
+    int tok = 0;
+    if (valid) { kx = keys[idx]; tok = toks[idx]; }
+    bool gt, eq = false;
+    if (by_score) { gt = valid && kx > thr; eq = valid && kx == thr; }
+    else gt = valid && idx < m;
+    unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
+    int gt_before = __popcll(bgt & below), eq_before = __popcll(beq & below);
+    if (lane == 0) S.wtot[0][w] = make_int2(__popcll(bgt), __popcll(beq));
+    __syncthreads();
+    int tot_gt = 0, tot_eq = 0;
+#pragma unroll
+    for (int q = 0; q < SS_WAVES; ++q) {
+      const int2 t = S.wtot[0][q];
+      if (q < w) { gt_before += t.x; eq_before += t.y; }
+      tot_gt += t.x; tot_eq += t.y;
+    }
+    if (valid) {
+      int eqs = run_eq + eq_before;                       // equal keys before this one
+      if (gt || (eq && (u32)eqs < need_eq)) {
+        int sl = fill0 + run_gt + gt_before + min(eqs, (int)need_eq);
+        slot[(size_t)tok * (A.k + 1) + r] = sl;
+        slot_token[(size_t)j * A.C + sl] = tok;
+      }
+    }
+    run_gt += tot_gt;
+    run_eq += tot_eq;
+    __syncthreads();
+  }
+}
+
 // A selection list is the piece of a (round, expert) candidate array that competes for one capacity
 // block: the whole array and the expert's whole queue by default; with per-group quotas (Sec. 3's
 // capacity read per GPU) the candidates of group g - a contiguous piece, since candidates are in
@@ -330,35 +474,122 @@ __device__ inline u32 radix_select(int m, Each each, u32 *hist, u32 *s_pick, u32
 // (Fill-in, the (k+1)-th, included) is planned from the candidate counts alone; each workgroup derives
 // its own list's numbers from them, and the workgroup of an expert's last round and first block also
 // writes the expert's fill counts.
+//
+// Lists of up to SS_THREADS * SS_PER candidates are one workgroup's work (select_in_registers).  A
+// longer list - a skewed router sends most tokens to a few experts - is cut into segments of
+// kSegLen candidates, one workgroup each (the first workgroups of the grid are the segments after a
+// list's first; each derives its (list, segment) from the candidate counts):
+//   * nobody, everybody or the first m in token order kept: a candidate's slot follows from its
+//     position alone, the segments need nothing from each other;
+//   * the m highest scores kept: every segment workgroup takes the same strided sample of the
+//     list's keys and selects in it a key L that, with a margin of several standard deviations,
+//     lies below the list's m-th highest key; it then copies its segment's candidates with key >= L,
+//     in order, to a second pair of arrays and counts them.  The workgroup that finishes last
+//     (a ticket from an atomic counter - nobody waits for anybody) adds up the counts: if they
+//     number at least m and fit the registers, the kept set is among them and it finishes the
+//     list with select_in_registers; otherwise (the sample misled, or the scores are tied en
+//     masse) it streams the original list.  The result is exact either way.
+constexpr int kSegLen = kSelectSegLen;           // 16384
+constexpr int kSegPer = kSegLen / SS_THREADS;    // candidates per thread of a segment workgroup
+constexpr int kSampleLen = kSegLen;              // keys in the sample
+constexpr int kRegMax = kSelectRegMax;           // candidates that fit the registers of one workgroup
+constexpr int kMapLists = 2048;                  // lists up to which long lists are split (the map is kept in LDS)
+
+// Exclusive scan of one value per thread over the workgroup (two barriers); total = sum over all threads.
+__device__ inline int block_scan_exclusive(int v, int *s_wave, int &total) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  int incl = v;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int t = __shfl_up(incl, off);
+    if (lane >= off) incl += t;
+  }
+  if (lane == 63) s_wave[w] = incl;
+  __syncthreads();
+  int before = 0;
+  total = 0;
+#pragma unroll
+  for (int q = 0; q < SS_WAVES; ++q) {
+    const int t = s_wave[q];
+    if (q < w) before += t;
+    total += t;
+  }
+  __syncthreads();
+  return before + incl - v;
+}
+
 __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A, const int32_t *__restrict__ cat_cnt,
                                                                  const int32_t *__restrict__ blk_off,
                                                                  const u32 *__restrict__ cand_key,
                                                                  const int32_t *__restrict__ cand_tok,
+                                                                 u32 *__restrict__ comp_key,
+                                                                 int32_t *__restrict__ comp_tok,
+                                                                 int32_t *__restrict__ seg_cnt,
+                                                                 int32_t *__restrict__ list_done,
                                                                  int32_t *__restrict__ slot,
                                                                  int32_t *__restrict__ slot_token,
                                                                  int32_t *__restrict__ grp_fill,
                                                                  int32_t *__restrict__ grp_off,
                                                                  int32_t *__restrict__ fill_topk,
                                                                  int32_t *__restrict__ fill_total) {
-  __shared__ u32 hist[kHistWords];
-  __shared__ u32 s_pick[2];
-  __shared__ int2 wtot[SS_PER][SS_WAVES];  // (kept-for-sure, equal-to-threshold) counts per (trip, wave)
-  __shared__ int2 wsum[8];
-  // list = (round r, expert j, capacity block g); n candidates, m of them kept, in slots fill0 ..
-  const int lst = blockIdx.x, cat = lst / A.Gq, g = lst - cat * A.Gq, r = cat / A.E, j = cat - r * A.E;
+  __shared__ SelectSmem S;
+  __shared__ int s_extra[kMapLists + 1];  // exclusive scan over the lists of their segments after the first
+  __shared__ int s_wave[SS_WAVES];
+  __shared__ int s_bcast;
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int bpg = A.NB / A.Gq * A.cb;  // count blocks per group (exact with quotas; all of them otherwise)
-  // candidates [lo, hi) of (round rr, expert j) that belong to group gg
-  auto piece = [&](int rr, int gg, int &lo, int &hi) {
-    const int c = rr * A.E + j;
+  // candidates [lo, hi) of (round rr, expert jj) that belong to group gg
+  auto piece = [&](int rr, int jj, int gg, int &lo, int &hi) {
+    const int c = rr * A.E + jj;
     lo = gg == 0 ? 0 : blk_off[(size_t)c * A.NBc + gg * bpg];
     hi = gg == A.Gq - 1 ? cat_cnt[c] : blk_off[(size_t)c * A.NBc + (gg + 1) * bpg];
   };
+
+  // ---- which (list, segment) is this workgroup.  The workgroups of the further segments come first
+  // in the grid (those that turn out to have no segment leave at once): a split list is finished
+  // by the last of its segments, so they should not queue behind the one-workgroup lists.
+  const bool can_split = select_splits(A.T, A.NR, A.NL);  // otherwise the grid has one workgroup per list
+  const int n_extra = (int)gridDim.x - A.NL;
+  int lst = (int)blockIdx.x - n_extra, seg = 0, extra_base = 0;
+  if (can_split) {
+    int carry = 0;
+    for (int l0 = 0; l0 < A.NL; l0 += SS_THREADS) {
+      const int l = l0 + tid;
+      int ex = 0;
+      if (l < A.NL) {
+        const int c = l / A.Gq, gg = l - c * A.Gq, rr = c / A.E;
+        int lo, hi;
+        piece(rr, c - rr * A.E, gg, lo, hi);
+        ex = hi - lo > kRegMax ? (hi - lo + kSegLen - 1) / kSegLen - 1 : 0;
+      }
+      int total;
+      const int excl = block_scan_exclusive(ex, s_wave, total);
+      if (l < A.NL) s_extra[l] = carry + excl;
+      carry += total;
+    }
+    if (tid == 0) s_extra[A.NL] = carry;
+    __syncthreads();
+    if ((int)blockIdx.x < n_extra) {
+      const int x = blockIdx.x;
+      if (x >= s_extra[A.NL]) return;  // no such segment
+      int a = 0, b = A.NL - 1;  // the last list whose scan value is <= x (lists without extra segments repeat their successor's value)
+      while (a < b) {
+        const int mid = (a + b + 1) >> 1;
+        if (s_extra[mid] <= x) a = mid; else b = mid - 1;
+      }
+      lst = a;
+      seg = x - s_extra[lst] + 1;
+    }
+    extra_base = s_extra[lst];
+  }
+
+  // ---- the list: (round r, expert j, capacity block g); n candidates, m of them kept, in slots fill0 ..
+  const int cat = lst / A.Gq, g = lst - cat * A.Gq, r = cat / A.E, j = cat - r * A.E;
   int n = 0, m = 0, fill = 0, lo = 0;
   for (int rr = 0; rr <= r; ++rr) {
     int hi;
     fill += m;
-    piece(rr, g, lo, hi);
+    piece(rr, j, g, lo, hi);
     n = hi - lo;
     m = min(n, A.Cq - fill);
   }
@@ -367,162 +598,171 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
   for (int jj = 0; jj < j; ++jj) base += cat_cnt[r * A.E + jj];
   const u32 *keys = cand_key + base;
   const int32_t *toks = cand_tok + base;
-  if (r == A.NR - 1 && g == 0 && w == 0) {
-    // lane gg: occupied slots of block gg after the top-k rounds and after every round
-    int topk = 0, total = 0;
-    if (lane < A.Gq) {
-      for (int rr = 0; rr < A.NR; ++rr) {
-        int l, h;
-        piece(rr, lane, l, h);
-        total += min(h - l, A.Cq - total);
-        if (rr == A.k - 1) topk = total;
+  if (seg == 0) {
+    if (r == A.NR - 1 && g == 0 && w == 0) {
+      // lane gg: occupied slots of block gg after the top-k rounds and after every round
+      int topk = 0, total = 0;
+      if (lane < A.Gq) {
+        for (int rr = 0; rr < A.NR; ++rr) {
+          int l, h;
+          piece(rr, j, lane, l, h);
+          total += min(h - l, A.Cq - total);
+          if (rr == A.k - 1) topk = total;
+        }
       }
-    }
-    int incl = total, sum_topk = topk;
+      int incl = total, sum_topk = topk;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const int t = __shfl_up(incl, off);
-      if (lane >= off) incl += t;
-    }
+      for (int off = 1; off < 64; off <<= 1) {
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
+      }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) sum_topk += __shfl_xor(sum_topk, off);
-    if (lane < A.Gq) {
-      grp_fill[j * A.Gq + lane] = total;
-      grp_off[j * A.Gq + lane] = incl - total;
+      for (int off = 32; off > 0; off >>= 1) sum_topk += __shfl_xor(sum_topk, off);
+      if (lane < A.Gq) {
+        grp_fill[j * A.Gq + lane] = total;
+        grp_off[j * A.Gq + lane] = incl - total;
+      }
+      if (lane == 63) fill_total[j] = incl;
+      if (lane == 0) fill_topk[j] = sum_topk;
     }
-    if (lane == 63) fill_total[j] = incl;
-    if (lane == 0) fill_topk[j] = sum_topk;
+    // the last round pads the rest of the capacity block (Sec. 3: zero padding)
+    if (r == A.NR - 1)
+      for (int sl = fill0 + m + tid; sl < (g + 1) * A.Cq; sl += SS_THREADS) slot_token[(size_t)j * A.C + sl] = -1;
   }
+  if (m == 0) return;  // nobody kept: every slot entry already says so
   const bool by_score = !A.arrival || r == A.k;  // the Fill-in round always selects by score (Sec. 4.2)
-  const unsigned long long below = (1ull << lane) - 1ull;
-
-  // mode 0: nobody kept; 1: everybody kept; 2: the first m in token order; 3: by score threshold
-  const int mode = m == 0 ? 0 : (m == n ? 1 : (by_score ? 3 : 2));
-  u32 thr = 0, need_eq = 0;
-
-  if (n <= SS_THREADS * SS_PER) {
-    // Register path: candidate idx = u * SS_THREADS + tid is element u of thread tid.  Keys are read
-    // once; the four digit passes run on registers; the token-order prefix of the kept flags is one
-    // scan over the (trip, wave) totals instead of a barrier pair per trip.
-    const int nu = (n + SS_THREADS - 1) / SS_THREADS;
-    u32 kreg[SS_PER];
-    int treg[SS_PER];
-#pragma unroll
-    for (int u = 0; u < SS_PER; ++u) {
-      const int idx = u * SS_THREADS + tid;
-      kreg[u] = 0;
-      treg[u] = 0;
-      if (u < nu && idx < n) {
-        if (mode == 3) kreg[u] = keys[idx];
-        treg[u] = toks[idx];
-      }
+  const bool is_long = n > kRegMax;          // then, if can_split, the list has a workgroup per segment
+  if (m == n || !by_score) {
+    // everybody, or the first m in token order: slot = position
+    const bool cut = is_long && can_split;
+    const int i0 = cut ? seg * kSegLen : 0, i1 = min(m, cut ? i0 + kSegLen : n);
+    for (int idx = i0 + tid; idx < i1; idx += SS_THREADS) {
+      const int tok = toks[idx];
+      slot[(size_t)tok * (A.k + 1) + r] = fill0 + idx;
+      slot_token[(size_t)j * A.C + fill0 + idx] = tok;
     }
-    if (mode == 3)
-      thr = radix_select(m, [&](auto f) {
-#pragma unroll
-        for (int u = 0; u < SS_PER; ++u)
-          if (u < nu) f(kreg[u], u * SS_THREADS + tid < n);
-      }, hist, s_pick, need_eq);
+    return;
+  }
+  if (!is_long) {
+    select_in_registers(A, n, m, true, r, j, fill0, [&](int idx, u32 &kx, int &tok) { kx = keys[idx]; tok = toks[idx]; },
+                        S, slot, slot_token);
+    return;
+  }
 
-    int pre[SS_PER];  // lanes of this wave before this one: kept-for-sure | equal << 8
+  // ---- long list, the m highest scores: sample, copy the candidates that may be kept, last one finishes
+  const int nseg = (n + kSegLen - 1) / kSegLen;
+  // rank in the sample: the expected number of sampled keys among the list's m highest, plus five
+  // standard deviations and a few; the candidates with key >= L then number about n / kSampleLen times that
+  const float expect = (float)m * (float)kSampleLen / (float)n;
+  const int qsel = (int)(expect + 5.0f * sqrtf(expect) + 16.0f);
+  const bool split = can_split && qsel < kSampleLen && (long long)qsel * n / kSampleLen <= kRegMax * 7 / 8;
+  if (!split) {
+    if (seg == 0) select_streaming(A, n, m, true, r, j, fill0, keys, toks, S, slot, slot_token);
+    return;
+  }
+  u32 L;
+  {
+    const int stride = n / kSampleLen;  // >= 1: n > kRegMax > kSampleLen
+    u32 sk[kSegPer];
 #pragma unroll
-    for (int u = 0; u < SS_PER; ++u) {
-      pre[u] = 0;
-      if (u < nu) {
-        const int idx = u * SS_THREADS + tid;
-        const bool valid = idx < n;
-        bool gt, eq = false;
-        if (mode == 3) { gt = valid && kreg[u] > thr; eq = valid && kreg[u] == thr; }
-        else if (mode == 2) gt = valid && idx < m;
-        else gt = valid && mode == 1;
-        const unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
-        pre[u] = __popcll(bgt & below) | (__popcll(beq & below) << 8) | (gt ? 1 << 16 : 0) | (eq ? 1 << 17 : 0);
-        if (lane == 0) wtot[u][w] = make_int2(__popcll(bgt), __popcll(beq));
-      }
+    for (int u = 0; u < kSegPer; ++u) sk[u] = keys[(size_t)(u * SS_THREADS + tid) * stride];
+    u32 dummy;
+    L = radix_select(qsel, [&](auto f) {
+#pragma unroll
+      for (int u = 0; u < kSegPer; ++u) f(sk[u], true);
+    }, S.hist, S.pick, dummy);
+  }
+  {
+    const unsigned long long below = (1ull << lane) - 1ull;
+    const int i0 = seg * kSegLen, len = min(n - i0, kSegLen);
+    u32 kreg[kSegPer];
+    int pre[kSegPer];
+#pragma unroll
+    for (int u = 0; u < kSegPer; ++u) {
+      const int idx = u * SS_THREADS + tid;
+      kreg[u] = idx < len ? keys[i0 + idx] : 0u;
+      const bool ge = idx < len && kreg[u] >= L;
+      const unsigned long long bge = __ballot(ge);
+      pre[u] = __popcll(bge & below) | (ge ? 1 << 16 : 0);
+      if (lane == 0) S.wtot[u][w] = make_int2(__popcll(bge), 0);
     }
     __syncthreads();
-    // exclusive scan of the nu * SS_WAVES totals in (trip, wave) order = token order
-    const int ne = nu * SS_WAVES;
-    int2 mine = make_int2(0, 0), incl = mine;
-    if (tid < ne) mine = (&wtot[0][0])[tid];
-    if (tid < 8 * kWave) {  // SS_PER * SS_WAVES = 384 entries fit 6 waves
+    // exclusive scan of the kSegPer * SS_WAVES wave totals in (trip, wave) order = token order
+    int mine = 0, incl = 0;
+    if (tid < kSegPer * SS_WAVES) mine = (&S.wtot[0][0])[tid].x;
+    if (tid < 4 * kWave) {  // kSegPer * SS_WAVES = 256 entries = 4 waves
       incl = mine;
 #pragma unroll
       for (int off = 1; off < 64; off <<= 1) {
-        const int tx = __shfl_up(incl.x, off), ty = __shfl_up(incl.y, off);
-        if (lane >= off) { incl.x += tx; incl.y += ty; }
+        const int t = __shfl_up(incl, off);
+        if (lane >= off) incl += t;
       }
-      if (lane == 63) wsum[w] = incl;
+      if (lane == 63) S.wsum[w].x = incl;
     }
     __syncthreads();
-    if (tid < ne) {
-      int2 before = make_int2(0, 0);
-      for (int q = 0; q < w; ++q) { before.x += wsum[q].x; before.y += wsum[q].y; }
-      (&wtot[0][0])[tid] = make_int2(before.x + incl.x - mine.x, before.y + incl.y - mine.y);
+    int count = 0;
+    if (tid < kSegPer * SS_WAVES) {
+      int before = 0;
+      for (int q = 0; q < w; ++q) before += S.wsum[q].x;
+      (&S.wtot[0][0])[tid].x = before + incl - mine;
     }
+    count = S.wsum[0].x + S.wsum[1].x + S.wsum[2].x + S.wsum[3].x;
     __syncthreads();
 #pragma unroll
-    for (int u = 0; u < SS_PER; ++u) {
-      if (u < nu && u * SS_THREADS + tid < n) {
-        const int2 base = wtot[u][w];
-        const bool gt = (pre[u] >> 16) & 1, eq = (pre[u] >> 17) & 1;
-        const int eqs = base.y + ((pre[u] >> 8) & 255);  // equal keys before this one
-        const bool kept = gt || (eq && (u32)eqs < need_eq);
-        const int sl = fill0 + base.x + (pre[u] & 255) + min(eqs, (int)need_eq);
-        if (kept) {
-          slot[(size_t)treg[u] * (A.k + 1) + r] = sl;
-          slot_token[(size_t)j * A.C + sl] = treg[u];
-        }
+    for (int u = 0; u < kSegPer; ++u) {
+      if ((pre[u] >> 16) & 1) {
+        const int idx = u * SS_THREADS + tid, pos = base + i0 + S.wtot[u][w].x + (pre[u] & 255);
+        comp_key[pos] = kreg[u];
+        comp_tok[pos] = toks[i0 + idx];
       }
     }
-  } else {
-    if (mode == 3)
-      thr = radix_select(m, [&](auto f) {
-        for (int base = 0; base < n; base += SS_THREADS) {
-          const int idx = base + tid;
-          f(idx < n ? keys[idx] : 0u, idx < n);
-        }
-      }, hist, s_pick, need_eq);
-    int run_gt = 0, run_eq = 0;
-    for (int base = 0; base < n; base += SS_THREADS) {
-      const int idx = base + tid;
-      const bool valid = idx < n;
-      u32 kx = 0;
-      int tok = 0;
-      if (valid) { kx = keys[idx]; tok = toks[idx]; }
-      bool gt, eq = false;
-      if (mode == 3) { gt = valid && kx > thr; eq = valid && kx == thr; }
-      else if (mode == 2) gt = valid && idx < m;
-      else gt = valid && mode == 1;
-      unsigned long long bgt = __ballot(gt), beq = __ballot(eq);
-      int gt_before = __popcll(bgt & below), eq_before = __popcll(beq & below);
-      if (lane == 0) wtot[0][w] = make_int2(__popcll(bgt), __popcll(beq));
-      __syncthreads();
-      int tot_gt = 0, tot_eq = 0;
-#pragma unroll
-      for (int q = 0; q < SS_WAVES; ++q) {
-        const int2 t = wtot[0][q];
-        if (q < w) { gt_before += t.x; eq_before += t.y; }
-        tot_gt += t.x; tot_eq += t.y;
-      }
-      if (valid) {
-        int eqs = run_eq + eq_before;                       // equal keys before this one
-        bool kept = gt || (eq && (u32)eqs < need_eq);
-        int kept_before = run_gt + gt_before + min(eqs, (int)need_eq);
-        int sl = fill0 + kept_before;
-        if (kept) {
-          slot[(size_t)tok * (A.k + 1) + r] = sl;
-          slot_token[(size_t)j * A.C + sl] = tok;
-        }
-      }
-      run_gt += tot_gt;
-      run_eq += tot_eq;
-      __syncthreads();
+    // publish: count, then the ticket.  Every wave waits until its own copies have been written (a
+    // store counts as done when the L2 has it), the barrier collects the waves, and ONE device-scope
+    // fence (a write-back of the L2, which the other XCDs do not see into) goes before the ticket.
+    // Whoever draws the last ticket fences once more before it reads the other segments' copies.
+    const int seg_id = seg == 0 ? lst : A.NL + extra_base + seg - 1;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (tid == 0) {
+      seg_cnt[seg_id] = count;
+      __threadfence();
+      s_bcast = atomicAdd(&list_done[lst], 1);
+      if (s_bcast == nseg - 1) __threadfence();
     }
+    __syncthreads();
+    if (s_bcast != nseg - 1) return;
   }
-  // the last round pads the rest of the capacity block (Sec. 3: zero padding)
-  if (r == A.NR - 1)
-    for (int sl = fill0 + m + tid; sl < (g + 1) * A.Cq; sl += SS_THREADS) slot_token[(size_t)j * A.C + sl] = -1;
+  // ---- the last workgroup of the list: segments' counts -> offsets of their copies (s_extra is free now)
+  __syncthreads();
+  int total = 0;
+  {
+    int carry = 0;
+    for (int q0 = 0; q0 < nseg; q0 += SS_THREADS) {  // nseg <= 2^24 / kSegLen + 1 fits s_extra
+      const int q = q0 + tid;
+      const int c = q < nseg ? seg_cnt[q == 0 ? lst : A.NL + extra_base + q - 1] : 0;
+      int tot;
+      const int excl = block_scan_exclusive(c, s_wave, tot);
+      if (q < nseg) s_extra[q] = carry + excl;
+      carry += tot;
+    }
+    total = carry;
+    __syncthreads();
+  }
+  if (total < m || total > kRegMax) {
+    select_streaming(A, n, m, true, r, j, fill0, keys, toks, S, slot, slot_token);
+    return;
+  }
+  const int *s_off = s_extra;  // first copy of every segment
+  select_in_registers(A, total, m, true, r, j, fill0, [&](int idx, u32 &kx, int &tok) {
+    int a = 0, b = nseg - 1;  // segment whose copies hold position idx
+    while (a < b) {
+      const int mid = (a + b + 1) >> 1;
+      if (s_off[mid] <= idx) a = mid; else b = mid - 1;
+    }
+    const int pos = base + a * kSegLen + (idx - s_off[a]);
+    kx = comp_key[pos];
+    tok = comp_tok[pos];
+  }, S, slot, slot_token);
 }
 
 // ------------------------------------------------------------------ select_slot, small batches
@@ -873,15 +1113,19 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     prof_end(K_SELECT_SLOT, s);
   } else {
     prof_begin(K_SCAN_CAND, s);
-    scan_blocks_kernel<<<D.NCAT, SC_THREADS, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NBc);
+    // (also clears the tickets of the lists' segments: Gq lists per candidate array)
+    scan_blocks_kernel<<<D.NCAT, SC_THREADS, 0, s>>>(W.blk_cnt, W.cat_cnt, D.NBc, W.list_done, D.Gq);
     prof_end(K_SCAN_CAND, s);
     prof_begin(K_SCATTER_CAND, s);
     scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_cnt, W.cand_key,
                                                          W.cand_tok, tb.slot);
     prof_end(K_SCATTER_CAND, s);
     prof_begin(K_SELECT_SLOT, s);
-    select_slot_kernel<<<D.NL, SS_THREADS, 0, s>>>(A, W.cat_cnt, W.blk_cnt, W.cand_key, W.cand_tok, tb.slot,
-                                                   tb.slot_token, W.grp_fill, W.grp_off, tb.fill_topk, tb.fill_total);
+    // one workgroup per list, plus one for every further segment that a long list can have
+    const int sel_grid = D.NL + (select_splits(D.T, D.NR, D.NL) ? (int)((long long)D.T * D.NR / kSelectSegLen) : 0);
+    select_slot_kernel<<<sel_grid, SS_THREADS, 0, s>>>(A, W.cat_cnt, W.blk_cnt, W.cand_key, W.cand_tok, W.comp_key,
+                                                       W.comp_tok, W.seg_cnt, W.list_done, tb.slot, tb.slot_token,
+                                                       W.grp_fill, W.grp_off, tb.fill_topk, tb.fill_total);
     prof_end(K_SELECT_SLOT, s);
   }
   if (D.ir) {
@@ -890,7 +1134,7 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     prof_end(K_IR_COUNT, s);
     if (!A.ir_self) {
       prof_begin(K_IR_SCAN, s);
-      scan_blocks_kernel<<<D.E, SC_THREADS, 0, s>>>(W.ir_blk_cnt, W.ir_cnt, D.NB);
+      scan_blocks_kernel<<<D.E, SC_THREADS, 0, s>>>(W.ir_blk_cnt, W.ir_cnt, D.NB, nullptr, 0);
       prof_end(K_IR_SCAN, s);
     }
   }

@@ -14,6 +14,14 @@ constexpr int kMaxK = 4;
 constexpr int kMaxRounds = kMaxK + 1;   // k top-k rounds + the Fill-in round
 constexpr int kTokBlock = 128;          // tokens per workgroup in the per-token routing kernels
 constexpr int kWave = 64;
+// Selection lists (rr_dispatch.hip): up to kSelectRegMax candidates are one workgroup's registers;
+// longer lists are cut into segments of kSelectSegLen candidates, one workgroup each, when the batch
+// can hold such a list at all and the lists are few enough for the segment map (kept in LDS).
+constexpr int kSelectRegMax = 24576;
+constexpr int kSelectSegLen = 16384;
+__host__ __device__ inline bool select_splits(long long T, int NR, int NL) {
+  return T * NR > kSelectRegMax && NL <= 2048;
+}
 
 typedef uint32_t u32;
 
@@ -58,6 +66,10 @@ struct Work {
   int32_t *row_token;    // [Rmax]    per-group quotas only: token of every dispatched row
   u32     *cand_key;     // [NR*T]    per-list candidates in ascending token index
   int32_t *cand_tok;     // [NR*T]
+  u32     *comp_key;     // [NR*T]    split lists only: per segment, the candidates that may be kept, in order
+  int32_t *comp_tok;     // [NR*T]
+  int32_t *seg_cnt;      // [NL + NR*T / kSelectSegLen] how many of those every segment has
+  int32_t *list_done;    // [NL]      segments of a list that have finished (tickets)
   int32_t *ir_blk_cnt;   // [E, NB]   Intra-GPU tokens per (expert, token block); scanned in place
   int32_t *ir_cnt;       // [E]
   int32_t *row_base;     // [E+1]     first dispatched row of each expert (slot rows, then IR rows)

@@ -117,6 +117,27 @@ def test_dispatch_deterministic():
             assert np.array_equal(first[name], again[name]), name
 
 
+LONG_LIST_CASES = [
+    # T, E, G, k, cf, bias of expert 1, ties, arrival, quota
+    (300000, 8, 2, 2, 0.5, 4.0, False, False, False),   # one expert draws ~all first choices: a list of ~290 K candidates, split
+    (300032, 8, 2, 1, 1.0, 4.0, True, False, False),    # the same with scores tied en masse: the sample cannot separate them
+    (200000, 4, 2, 2, 3.0, 3.0, False, False, False),   # long lists kept whole (capacity above the candidates)
+    (262144, 8, 2, 2, 0.75, 4.0, False, True, False),   # long lists, arrival order
+    (4 * 65536, 4, 4, 1, 0.4, 5.0, False, False, True), # per-group capacity: every group's piece of the array is long
+    (500000, 64, 8, 2, 0.75, 2.0, False, False, False), # 64 experts, moderate skew: long and short lists side by side
+]
+
+
+@pytest.mark.parametrize("T,E,G,k,cf,hot,ties,arrival,quota", LONG_LIST_CASES)
+def test_dispatch_long_lists_bit_exact(T, E, G, k, cf, hot, ties, arrival, quota):
+    """Selection lists far longer than one workgroup's registers (a skewed router): tables bit-exact."""
+    a = wl.synthetic_logits(T, E, seed=T % 1000 + E, bias_std=0.5, ties=ties)
+    a[:, 1] += np.float32(hot)
+    a[:, min(3, E - 1)] += np.float32(hot / 2)
+    cfg = rr.RRConfig(T, 64, 0, E, k, G, cf, rr.RR_F32, rr.RR_ACT_SWIGLU, gu.flags_of(("ir", "fr"), arrival, quota))
+    gu.assert_tables_equal(gu.run_dispatch(cfg, a), _oracle_tables(a, cfg, ("ir", "fr"), arrival, quota))
+
+
 # ------------------------------------------------------------------ router scores
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 @pytest.mark.parametrize("T,d,E,k", [(256, 64, 8, 1), (1000, 264, 6, 2), (513, 1024, 64, 2), (2048, 2048, 16, 1)])
