@@ -155,7 +155,7 @@ int rr_rectified_dispatch(const rr_config *cfg, const float *logits, const rr_ta
  * library's device image (one copy per GPU the library runs on, held until the process ends).  The
  * call allocates nothing.  A configuration whose rr_workspace_bytes (with d_ff = 0) exceeds
  * RR_STATIC_WORKSPACE_BYTES is refused with RR_ERR_TOO_LARGE before anything is launched (at
- * k = 2 with Fill-in and 64 experts that is about 600 K tokens).  All calls on one GPU share
+ * k = 2 with Fill-in and 64 experts that is about 440 K tokens).  All calls on one GPU share
  * that GPU's buffer: calls that overlap on one GPU - two streams, two host threads - race; issue
  * them on one stream.  Nothing in the buffer needs to start at zero (every kernel writes what the
  * next one reads), so the contents left by an earlier call do not matter. */
