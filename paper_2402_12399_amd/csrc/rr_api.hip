@@ -25,6 +25,7 @@ static int device_setup() {
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return -1;
   std::call_once(g_dev_once[dev], [dev] {
     hipError_t e = ffn_kernel_attributes();
+    if (e == hipSuccess) e = router_kernel_attributes();
     void *p = nullptr;
     if (e == hipSuccess) e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
     g_scratch_ptr[dev] = e == hipSuccess ? p : nullptr;
@@ -246,6 +247,7 @@ int rr_router_scores(const rr_config *cfg, const void *x, const float *w_router,
   if (!aligned16(x) || !aligned16(w_router) || !aligned16(logits) || !aligned16(probs) || !aligned4(bias) ||
       !aligned4(rank_expert))
     return RR_ERR_INVALID_ARG;
+  if (device_setup() < 0) return RR_ERR_HIP;
   hipError_t e = launch_router(D, x, w_router, bias, logits, probs, rank_expert, nullptr, nullptr,
                                static_cast<hipStream_t>(stream));
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
@@ -307,7 +309,7 @@ int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, c
   memset(&W, 0, sizeof(W));
   rc = check_ws(D, !routing_only, workspace, workspace_bytes, &W);
   if (rc != RR_OK) return rc;
-  if (!routing_only && device_setup() < 0) return RR_ERR_HIP;
+  if (device_setup() < 0) return RR_ERR_HIP;
   hipStream_t s = static_cast<hipStream_t>(stream);
   const rr_tables &tb = tables ? *tables : W.tables;
   float *lg = logits ? logits : W.logits;

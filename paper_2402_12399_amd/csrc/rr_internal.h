@@ -119,6 +119,7 @@ hipError_t launch_router(const Dims &D, const void *x, const float *w_router, co
 hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, bool ranked,
                            hipStream_t s);
 hipError_t launch_gather(const Dims &D, const void *x, const rr_tables &tb, const Work &W, hipStream_t s);
+hipError_t router_kernel_attributes();  // raises the dynamic-LDS limit of the streaming router on the current device
 hipError_t ffn_kernel_attributes();     // raises the dynamic-LDS limit of the bf16 GEMM kernels on the current device
 bool ffn_fuses_gather(const Dims &D);  // the up projection reads x through the dispatch tables: no gather pass
 hipError_t launch_ffn(const Dims &D, const void *x, const rr_tables &tb, const void *w1, const void *w3,

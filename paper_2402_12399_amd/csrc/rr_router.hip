@@ -348,197 +348,240 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
 }
 
 // ------------------------------------------------------------------ large batches
-// Streaming variant: a workgroup of 4 waves owns 256 tokens, each wave 64 of them over the whole K
-// (no K split, no reduction).  The router weights go through LDS: every 64-wide K chunk of w is
-// split into its three bf16 parts ONCE per workgroup (not once per wave) and stored as MFMA
-// operand rows (128-byte rows, chunk c of row r at position c ^ ((r >> 1) & 7), as in the grouped
-// GEMM); x still streams global -> registers, one K chunk (64 bytes per lane) ahead.  One barrier
-// per chunk.
-// With a RankOut the epilogue also does the per-token work that the routing tables start from
-// (see rank_row; candidate counts per 128-token block), so the logits are not read back from HBM.
+// Streaming kernel (no K split, no reduction): a workgroup of 4 waves owns 128 tokens - one block of
+// the routing kernels - and wave w the 32 tokens [32 w, 32 w + 32) over the whole K.
+//   * x takes the route of the grouped GEMM's operands: buffer_load ... lds, 16 bytes per lane
+//     straight into LDS, where a wave instruction covers 8 rows x 128 contiguous bytes (8 whole cache
+//     lines); the MFMA fragments are then read from LDS (ds_read_b128; rows of 128 bytes, piece c of
+//     row r at position c ^ ((r >> 1) & 7)).  Reading x with one row per lane, straight into the
+//     fragment registers, makes every wave instruction touch 64 different lines for 16 bytes each,
+//     and the rate at which the load unit looks lines up - not HBM - then bounds the kernel
+//     (measured: 4.1 TB/s of algorithmic bytes at 1M x 1024 fp32 tokens, against 4.3 here).  No
+//     registers hold x in flight, so the ring is as deep as LDS allows;
+//   * a wave's part of the ring is its own, filled and read by nobody else: x needs no barrier,
+//     the wave waits (counted, vmcnt) for its own loads.  Ring of XS stages of one K chunk (128
+//     bytes of every row); chunk c + XS - 1 is requested while chunk c is multiplied.  Rows past
+//     the batch and pieces past d_model lie outside the buffer range and read as zero; requests
+//     past the last chunk re-read the last chunk, so every chunk issues the same x loads and the
+//     counted wait holds for any shape;
+//   * the router weights go through LDS as well: every K chunk of w is split into its three bf16
+//     parts ONCE per workgroup and stored as MFMA operand rows (swizzled like x); the weights of
+//     chunk c + 2 are fetched (global -> registers) during chunk c and written to LDS at the end
+//     of chunk c + 1; two stages, one barrier per chunk;
+//   * two workgroups per CU (each about 74 KB of LDS): one's epilogue overlaps the other's stream;
+//   * the epilogue goes through a per-wave LDS tile; with a RankOut it also does the per-token work
+//     that the routing tables start from (see rank_row), so the logits are not read back from HBM.
+// What the compiler must not see: it makes every LDS load or store that follows an LDS-DMA load
+// wait for that load - the ring's youngest request - because it cannot tell the stages apart.
+// The fragment reads of x and the stores of the weight parts are therefore spelled out in assembly.
+constexpr int RX_TB = kTokBlock;  // tokens per workgroup
+static_assert(RX_TB == RT_NW * 32, "one 32-token fragment per wave");
 
-constexpr int RS_TM = 2;                     // 32-token fragments per wave
-constexpr int RS_TB = RT_NW * RS_TM * 32;    // 256 tokens per workgroup
-static_assert(RS_TB == 2 * kTokBlock, "a workgroup covers exactly two 128-token blocks of the routing kernels");
+template <bool BF16, int NJ>
+struct RxLayout {
+  static constexpr int KC = BF16 ? 64 : 32;          // K chunk: 128 bytes of a row of x
+  static constexpr int ROWS = NJ * 32;               // expert rows staged
+  static constexpr int ROWB = KC * 2;                // bytes of a staged bf16 weight row
+  static constexpr int PART = ROWS * ROWB;           // one bf16 part of a weight chunk
+  static constexpr int WSTAGE = 3 * PART;
+  static constexpr int XSTAGE = RX_TB * 128;         // one chunk of x for the workgroup: 16 KB
+  static constexpr int XS = 3;                       // ring depth
+  static constexpr int TSTR = ROWS + 1;
+  static constexpr int TILE_BYTES = RT_NW * 32 * TSTR * 4;  // epilogue tiles reuse the ring
+  static constexpr int X_BYTES = XS * XSTAGE > TILE_BYTES ? XS * XSTAGE : TILE_BYTES;
+  static constexpr int SMEM = X_BYTES + 2 * WSTAGE;
+};
 
-// EXACT: d is a whole number of four-chunk ring trips and E fills the staged rows.  No load needs a
-// predicate and none sits behind a branch (prefetches past the last chunk re-read the last chunk
-// instead), so every chunk issues the same loads and the compiler's counted waits stay exact: a
-// chunk waits for its own data only, not for the three chunks in flight behind it.
-template <bool BF16, int NJ, bool FUSE, bool EXACT>
-__global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *__restrict__ xv,
+template <bool BF16, int NJ, bool FUSE>
+__global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *__restrict__ xv,
                                                                    const float *__restrict__ wr,
                                                                    const float *__restrict__ bias,
                                                                    float *__restrict__ logits, float *__restrict__ probs,
                                                                    int32_t *__restrict__ rank_expert, int T, int d, int E,
                                                                    int k, RankOut R) {
-  constexpr int TM = RS_TM;
+#if defined(__HIP_DEVICE_COMPILE__)  // buffer-resource and LDS-DMA builtins exist in the device pass only
+  using L = RxLayout<BF16, NJ>;
   constexpr int ES = BF16 ? 2 : 4;
-  constexpr int KC = BF16 ? 64 : 32;          // K chunk: a lane covers KC/2 elements = 64 bytes of its row
-  constexpr int XQ = KC * ES / 32;            // uint4 loads per lane per fragment per chunk (= 4)
-  constexpr int ROWS = NJ * 32;               // expert rows staged
-  constexpr int ROWB = KC * 2;                // bytes of a staged bf16 row
-  constexpr int NCH = ROWB / 16;              // 16-byte chunks per row: 8 (swizzle (r>>1)&7) or 4 ((r>>2)&3)
-  constexpr int PART = ROWS * ROWB;           // bytes of one bf16 part of a chunk
-  constexpr int STAGE = 3 * PART;
+  constexpr int KC = L::KC, ROWS = L::ROWS, ROWB = L::ROWB, PART = L::PART, WSTAGE = L::WSTAGE, XSTAGE = L::XSTAGE;
+  constexpr int XS = L::XS, TSTR = L::TSTR;
+  constexpr int NCH = ROWB / 16;                     // 16-byte pieces per weight row: 8 (bf16 x) or 4 (fp32 x)
   constexpr int WLD = ROWS * (KC / 4) / RT_THREADS;  // float4 loads of w per thread per chunk
-  constexpr int TSTR = ROWS + 1;              // row stride of the per-wave [32 tokens][experts] epilogue tile
-  constexpr int TILE_BYTES = RT_NW * 32 * TSTR * 4;  // the epilogue tiles reuse the weight stages
-  __shared__ __attribute__((aligned(16))) char lds[2 * STAGE > TILE_BYTES ? 2 * STAGE : TILE_BYTES];
-  __shared__ int cnt[2][kMaxRounds * kMaxE];
+  constexpr int NX = 32 * 128 / 1024;                // LDS-DMA instructions per wave per chunk (4)
+  constexpr int KS = KC / 16;                        // MFMA k-steps per chunk
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+  __shared__ int cnt[kMaxRounds * kMaxE];
   __shared__ float row_max[RT_NW][32], row_inv[RT_NW][32];
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  char *const wst = lds + L::X_BYTES;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
-  auto swz = [](int r) { return NCH == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); };
-  const int fsw = swz(fr);
-  const int t0 = blockIdx.x * RS_TB, tw0 = t0 + w * TM * 32;
+  auto wswz = [](int r) { return NCH == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); };
+  const int fsw_w = wswz(fr), fsw_x = (fr >> 1) & 7;
+  const int t0 = blockIdx.x * RX_TB, tw0 = t0 + w * 32;
   const int nchunk = (d + KC - 1) / KC;
 
-  const char *xrow[TM];
+  // ---- x: this wave's 32 rows as a buffer (rows past the batch are outside its range)
+  const int rows_valid = max(0, min(32, T - tw0));
+  const __amdgpu_buffer_rsrc_t rsx = __builtin_amdgcn_make_buffer_rsrc(
+      const_cast<char *>(static_cast<const char *>(xv)) + (size_t)min(tw0, T - 1) * d * ES, 0,
+      __builtin_amdgcn_readfirstlane(rows_valid * d * ES), 0x00020000);
+  // instruction i fills LDS rows [8 i, 8 i + 8) of the wave's stage: lane l -> row 8 i + l / 8, position
+  // l % 8, i.e. it fetches piece (l % 8) ^ swizzle(row) of that row's chunk
+  int xoff[NX], xpiece[NX];
 #pragma unroll
-  for (int i = 0; i < TM; ++i)
-    xrow[i] = static_cast<const char *>(xv) + (size_t)min(tw0 + i * 32 + fr, T - 1) * d * ES;
+  for (int i = 0; i < NX; ++i) {
+    const int row = 8 * i + (lane >> 3);
+    xpiece[i] = (lane & 7) ^ ((row >> 1) & 7);
+    xoff[i] = row * d * ES + xpiece[i] * 16;
+  }
+  auto issue_x = [&](int c, int stage) {
+    char *st = lds + stage * XSTAGE + w * (32 * 128);
+    const int koff = c * 128;  // byte offset of chunk c in a row
+    const bool tail = (c + 1) * KC > d;  // the last chunk of a d_model that is not a multiple of KC
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+      auto lp = (__attribute__((address_space(3))) void *)(st + i * 1024);
+      const bool past = tail && c * KC + xpiece[i] * (16 / ES) >= d;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsx, lp, 16, past ? 0x7ffffff0 : xoff[i], koff, 0, 0);
+    }
+  };
 
-  // ---- w staging: thread owns float4 (4 consecutive k) number tid + 256 q of the [ROWS][KC] chunk
-  // Two register sets: the weights of chunk c+2 are fetched during chunk c and written to LDS at
-  // the end of chunk c+1.  Loads complete in order, so a weight load that had to be complete within
-  // its own chunk would also drain every x load issued before it and flatten the x ring.
+  // ---- w staging: thread owns float4 (4 consecutive k) number tid + 256 q of the [ROWS][KC] chunk.
+  // Out-of-range elements are fetched from a clamped address and zeroed when they are written to LDS
+  // (not where they are loaded: a use right behind the load would wait for every load in flight), so
+  // every chunk issues exactly WLD loads.
   float4 wbuf0[WLD], wbuf1[WLD];
   auto load_w = [&](int kc, float4 (&wreg)[WLD]) {
 #pragma unroll
     for (int q = 0; q < WLD; ++q) {
       const int idx = tid + q * RT_THREADS, e = idx / (KC / 4), kk = kc + (idx % (KC / 4)) * 4;
-      wreg[q] = (EXACT || (e < E && kk < d)) ? *reinterpret_cast<const float4 *>(wr + (size_t)e * d + kk)
-                                             : make_float4(0.f, 0.f, 0.f, 0.f);
+      wreg[q] = *reinterpret_cast<const float4 *>(wr + (size_t)min(e, E - 1) * d + min(kk, d - 4));
     }
   };
-  auto store_w = [&](int stage, const float4 (&wreg)[WLD]) {
-    char *st = lds + stage * STAGE;
+  auto store_w = [&](int stage, int kc, const float4 (&wreg)[WLD]) {
+    char *st = wst + stage * WSTAGE;
 #pragma unroll
     for (int q = 0; q < WLD; ++q) {
       const int idx = tid + q * RT_THREADS, e = idx / (KC / 4), f4 = idx % (KC / 4);
+      const float keep = (e < E && kc + f4 * 4 < d) ? 1.0f : 0.0f;  // d_model % 8 == 0: four elements are in or out together
       u32 h0, l0, m0, h1, l1, m1;
-      split3_pair(wreg[q].x, wreg[q].y, h0, l0, m0);
-      split3_pair(wreg[q].z, wreg[q].w, h1, l1, m1);
-      // 8 bytes (4 bf16) at k offset f4*4: 16-byte chunk f4/2, half f4%2
-      const int off = e * ROWB + (((f4 >> 1) ^ swz(e)) << 4) + (f4 & 1) * 8;
-      *reinterpret_cast<uint2 *>(st + off) = make_uint2(h0, h1);
-      *reinterpret_cast<uint2 *>(st + PART + off) = make_uint2(l0, l1);
-      *reinterpret_cast<uint2 *>(st + 2 * PART + off) = make_uint2(m0, m1);
+      split3_pair(wreg[q].x * keep, wreg[q].y * keep, h0, l0, m0);
+      split3_pair(wreg[q].z * keep, wreg[q].w * keep, h1, l1, m1);
+      const int off = e * ROWB + (((f4 >> 1) ^ wswz(e)) << 4) + (f4 & 1) * 8;
+      // ds_write_b64 spelled out: the compiler makes an LDS store wait for every LDS-DMA load in flight
+      // (it cannot tell the weight stages from the ring), which would drain the ring once per chunk
+      typedef u32 u32x2 __attribute__((ext_vector_type(2)));
+      const u32 a = (u32)(size_t)(__attribute__((address_space(3))) char *)(st + off);
+      const u32x2 ph = {h0, h1}, pl = {l0, l1}, pm = {m0, m1};
+      asm volatile("ds_write_b64 %0, %1" ::"v"(a), "v"(ph) : "memory");
+      asm volatile("ds_write_b64 %0, %1 offset:%2" ::"v"(a), "v"(pl), "n"(PART) : "memory");
+      asm volatile("ds_write_b64 %0, %1 offset:%2" ::"v"(a), "v"(pm), "n"(2 * PART) : "memory");
     }
   };
 
-  // x ring: chunk c is consumed from buffer c % 4 while chunks c+1 .. c+3 are in flight (one chunk of
-  // MFMAs is shorter than an HBM round trip; three are not)
-  uint4 xb0[TM][XQ], xb1[TM][XQ], xb2[TM][XQ], xb3[TM][XQ];
-  auto load_x = [&](int kc, uint4 (&dst)[TM][XQ]) {
-    const int k0 = kc + fh * (KC / 2);  // this lane's half of the chunk
+  f32x16 acc[NJ];
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+  for (int j = 0; j < NJ; ++j)
 #pragma unroll
-      for (int q = 0; q < XQ; ++q) {
-        const int kq = k0 + q * (16 / ES);
-        dst[i][q] = (EXACT || kq < d) ? *reinterpret_cast<const uint4 *>(xrow[i] + (size_t)kq * ES) : make_uint4(0, 0, 0, 0);
-      }
-  };
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
 
-  f32x16 acc[TM][NJ];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < NJ; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-  // one K chunk: x of this chunk is in `xc`; x of chunk c+3 is loaded into `xo`, the weights of
-  // chunk c+2 into `wo`; `wn` holds the weights of chunk c+1
-  auto chunk = [&](int c, uint4 (&xc)[TM][XQ], uint4 (&xo)[TM][XQ], float4 (&wn)[WLD], float4 (&wo)[WLD]) {
-    // Stage c & 1 is complete (own LDS writes: lgkmcnt 0; everybody's: barrier) and the other stage
-    // is no longer read.  Not __syncthreads(): its fence would also wait for the x loads in flight.
+  // one K chunk.  On entry: the weights of chunk c + 1 are in `wn` (registers); this chunk's weights are
+  // in LDS stage c & 1 once the barrier has passed; x of chunks c .. c + XS - 2 has been requested.
+  // Every chunk issues WLD weight loads and NX x loads.
+  auto chunk = [&](int c, float4 (&wn)[WLD], float4 (&wo)[WLD]) {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    const bool more = EXACT || c + 1 < nchunk;
-    if (EXACT) {
-      load_w(min(c + 2, nchunk - 1) * KC, wo);
-      load_x(min(c + 3, nchunk - 1) * KC, xo);
-    } else {
-      if (c + 2 < nchunk) load_w((c + 2) * KC, wo);
-      if (c + 3 < nchunk) load_x((c + 3) * KC, xo);
-    }
-    // the loads are issued here, ahead of this chunk's arithmetic, and the weights of the next chunk
-    // are touched after it: left alone, the scheduler sinks the former and hoists the latter until
-    // the two meet and nothing is in flight for long
+    load_w(min(c + 2, nchunk - 1) * KC, wo);
+    issue_x(min(c + XS - 1, nchunk - 1), (c + XS - 1) % XS);
     __builtin_amdgcn_sched_barrier(0);
-    const char *st = lds + (c & 1) * STAGE;
-    // lane (row fr, half fh) holds elements [fh*KC/2 + 8 m, +8) of the chunk at k-step m: 16-byte chunk (KC/16) fh + m
+    // x of chunk c was requested XS - 1 chunks ago and (XS - 1) NX x requests have been issued since:
+    // when no more loads than that are outstanding, it has landed (loads complete in order).  The
+    // weight loads are left out of the count on purpose - the compiler may move them across this
+    // wait in either direction, and counting a load that is not there would let the wait pass early;
+    // not counting one that is there only makes it wait for part of the next chunk's x as well.
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((XS - 1) * NX) : "memory");
+    const char *sw = wst + (c & 1) * WSTAGE;
+    // x fragments of the whole chunk, four 16-byte pieces per lane.  Read with ds_read_b128 spelled out:
+    // the compiler makes an LDS read that follows an LDS-DMA load wait for that very load, i.e. for
+    // the ring's youngest request.  LDS operations return in order; the wait below covers these reads.
+    const u32 sx = (u32)(size_t)(__attribute__((address_space(3))) char *)(lds + (c % XS) * XSTAGE + w * (32 * 128) + fr * 128);
+    typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+    u32x4 xq0, xq1, xq2, xq3;
+    asm volatile("ds_read_b128 %0, %1" : "=v"(xq0) : "v"(sx + (((4 * fh + 0) ^ fsw_x) << 4)) : "memory");
+    asm volatile("ds_read_b128 %0, %1" : "=v"(xq1) : "v"(sx + (((4 * fh + 1) ^ fsw_x) << 4)) : "memory");
+    asm volatile("ds_read_b128 %0, %1" : "=v"(xq2) : "v"(sx + (((4 * fh + 2) ^ fsw_x) << 4)) : "memory");
+    asm volatile("ds_read_b128 %0, %1" : "=v"(xq3) : "v"(sx + (((4 * fh + 3) ^ fsw_x) << 4)) : "memory");
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xq0), "+v"(xq1), "+v"(xq2), "+v"(xq3)::"memory");
+    const uint4 xq[4] = {make_uint4(xq0.x, xq0.y, xq0.z, xq0.w), make_uint4(xq1.x, xq1.y, xq1.z, xq1.w),
+                         make_uint4(xq2.x, xq2.y, xq2.z, xq2.w), make_uint4(xq3.x, xq3.y, xq3.z, xq3.w)};
 #pragma unroll
-    for (int m = 0; m < KC / 16; ++m) {
-      const int pos = (((KC / 16) * fh + m) ^ fsw) << 4;
+    for (int m = 0; m < KS; ++m) {
+      const int posw = ((KS * fh + m) ^ fsw_w) << 4;
       Frag wh[NJ], wl[NJ], wl2[NJ];
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        const char *rowp = st + (j * 32 + fr) * ROWB + pos;
+        const char *rowp = sw + (j * 32 + fr) * ROWB + posw;
         wh[j].v = *reinterpret_cast<const bf16x8 *>(rowp);
         wl[j].v = *reinterpret_cast<const bf16x8 *>(rowp + PART);
         wl2[j].v = *reinterpret_cast<const bf16x8 *>(rowp + 2 * PART);
       }
+      if (BF16) {
+        // lane (row fr, half fh) takes elements [32 fh + 8 m, +8): piece 4 fh + m
+        Frag xf;
+        xf.w[0] = xq[m].x; xf.w[1] = xq[m].y; xf.w[2] = xq[m].z; xf.w[3] = xq[m].w;
 #pragma unroll
-      for (int i = 0; i < TM; ++i) {
-        if (BF16) {
-          Frag xf;
-          xf.w[0] = xc[i][m].x; xf.w[1] = xc[i][m].y; xf.w[2] = xc[i][m].z; xf.w[3] = xc[i][m].w;
-#pragma unroll
-          for (int j = 0; j < NJ; ++j) {
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wl2[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wl[j].v, acc[i][j], 0, 0, 0);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wh[j].v, acc[i][j], 0, 0, 0);
-          }
-        } else {
-          Frag xh, xl;
-          split2x8(xc[i][2 * m], xc[i][2 * m + 1], xh, xl);
-#pragma unroll
-          for (int j = 0; j < NJ; ++j) acc[i][j] = mfma5(xh, xl, wh[j], wl[j], wl2[j], acc[i][j]);
+        for (int j = 0; j < NJ; ++j) {
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wl2[j].v, acc[j], 0, 0, 0);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wl[j].v, acc[j], 0, 0, 0);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wh[j].v, acc[j], 0, 0, 0);
         }
+      } else {
+        // elements [16 fh + 8 m, +8) of the chunk: pieces 4 fh + 2 m and the next
+        Frag xh, xl;
+        split2x8(xq[2 * m], xq[2 * m + 1], xh, xl);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[j] = mfma5(xh, xl, wh[j], wl[j], wl2[j], acc[j]);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
-    if (more) store_w((c + 1) & 1, wn);
+    store_w((c + 1) & 1, min(c + 1, nchunk - 1) * KC, wn);
   };
+  static_assert(XS == 3, "the prologue requests two chunks");
   load_w(0, wbuf0);
-  if (EXACT || 1 < nchunk) load_w(KC, wbuf1);
-  load_x(0, xb0);
-  if (EXACT || 1 < nchunk) load_x(KC, xb1);
-  if (EXACT || 2 < nchunk) load_x(2 * KC, xb2);
-  store_w(0, wbuf0);
-  for (int c = 0; c < nchunk; c += 4) {  // four chunks per trip: the rings rotate without register copies
-    chunk(c, xb0, xb3, wbuf1, wbuf0);
-    if (EXACT || c + 1 < nchunk) chunk(c + 1, xb1, xb0, wbuf0, wbuf1);
-    if (EXACT || c + 2 < nchunk) chunk(c + 2, xb2, xb1, wbuf1, wbuf0);
-    if (EXACT || c + 3 < nchunk) chunk(c + 3, xb3, xb2, wbuf0, wbuf1);
+  __builtin_amdgcn_sched_barrier(0);
+  issue_x(0, 0);
+  __builtin_amdgcn_sched_barrier(0);
+  load_w(min(1, nchunk - 1) * KC, wbuf1);
+  __builtin_amdgcn_sched_barrier(0);
+  issue_x(min(1, nchunk - 1), 1);
+  __builtin_amdgcn_sched_barrier(0);
+  store_w(0, 0, wbuf0);
+  for (int c = 0; c < nchunk; c += 2) {  // two chunks per trip: the weight registers alternate without copies
+    chunk(c, wbuf1, wbuf0);
+    if (c + 1 < nchunk) chunk(c + 1, wbuf0, wbuf1);
   }
-  __syncthreads();  // the weight stages become the epilogue tiles
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // requests past the last chunk have landed: the ring becomes the tiles
+  __syncthreads();
 
-  // ---- epilogue, one 32-token fragment at a time through this wave's LDS tile
+  // ---- epilogue through this wave's LDS tile
   float *tile = reinterpret_cast<float *>(lds) + w * 32 * TSTR;
   if (FUSE) {
-    for (int c = tid; c < 2 * kMaxRounds * kMaxE; c += RT_THREADS) (&cnt[0][0])[c] = 0;
+    for (int c = tid; c < kMaxRounds * kMaxE; c += RT_THREADS) cnt[c] = 0;
     __syncthreads();
   }
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-    const int tf0 = tw0 + i * 32;            // first token of the fragment
-    const int ntok = min(32, T - tf0);       // may be <= 0 for the last workgroup
+  {
+    const int tf0 = tw0;
+    const int ntok = min(32, T - tf0);  // may be <= 0 for the last workgroup
     // accumulator element v is token 8*(v/4) + 4*(lane/32) + v%4, expert lane%32
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
       const int e = j * 32 + fr;
       const float b = (bias && e < E) ? bias[e] : 0.0f;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) tile[(8 * (v >> 2) + 4 * fh + (v & 3)) * TSTR + e] = acc[i][j][v] + b;
+      for (int v = 0; v < 16; ++v) tile[(8 * (v >> 2) + 4 * fh + (v & 3)) * TSTR + e] = acc[j][v] + b;
     }
     __builtin_amdgcn_wave_barrier();
-    // logits rows of the fragment are contiguous in memory
-    if (EXACT) {
-      // E == ROWS: a lane stores four consecutive experts of a token, a wave 1 KB per instruction
+    if (E == ROWS) {
+      // a lane stores four consecutive experts of a token, a wave 1 KB per instruction
       constexpr int LPR = ROWS / 4;  // lanes per row
       const int r0 = lane / LPR, e0 = (lane % LPR) * 4;
 #pragma unroll
@@ -565,7 +608,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
         row_max[w][lane] = mx;
         row_inv[w][lane] = 1.0f / sum;
       }
-      if (rank_expert || FUSE) rank_row<FUSE>(row, tok, E, k, rank_expert, R, cnt[w >> 1]);
+      if (rank_expert || FUSE) rank_row<FUSE>(row, tok, E, k, rank_expert, R, cnt);
     }
     if (probs) {
       __builtin_amdgcn_wave_barrier();
@@ -574,16 +617,12 @@ __global__ __launch_bounds__(RT_THREADS) void router_stream_kernel(const void *_
         probs[(size_t)tf0 * E + idx] = expf(tile[row * TSTR + e] - row_max[w][row]) * row_inv[w][row];
       }
     }
-    __builtin_amdgcn_wave_barrier();
   }
   if (FUSE) {
     __syncthreads();
-    // waves 0,1 cover token block 2*blockIdx.x, waves 2,3 the next one
-    for (int c = tid; c < 2 * R.NCAT; c += RT_THREADS) {
-      const int half = c / R.NCAT, cat = c - half * R.NCAT, b = 2 * blockIdx.x + half;
-      if (b < R.NBc) R.blk_cnt[(size_t)cat * R.NBc + b] = cnt[half][cat];
-    }
+    for (int c = tid; c < R.NCAT; c += RT_THREADS) R.blk_cnt[(size_t)c * R.NBc + blockIdx.x] = cnt[c];
   }
+#endif
 }
 
 // Tokens per workgroup of the K-split kernel, in 32-token fragments: one for small batches, so that the
@@ -608,26 +647,40 @@ void launch_one(const Dims &D, const void *x, const float *w_router, const float
 template <bool BF16>
 void launch_stream(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits, float *probs,
                    int32_t *rank_expert, const RankOut *R, hipStream_t s) {
-  dim3 grid((D.T + RS_TB - 1) / RS_TB), block(RT_THREADS);
+  dim3 grid((D.T + RX_TB - 1) / RX_TB), block(RT_THREADS);
   RankOut none{};
-  const int KC = BF16 ? 64 : 32;
-#define RR_LAUNCH_STREAM(NJ, EXACT)                                                                                 \
-  do {                                                                                                              \
-    if (R) router_stream_kernel<BF16, NJ, true, EXACT><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs,      \
-                                                                               rank_expert, D.T, D.d, D.E, D.k, *R); \
-    else router_stream_kernel<BF16, NJ, false, EXACT><<<grid, block, 0, s>>>(x, w_router, bias, logits, probs,       \
-                                                                              rank_expert, D.T, D.d, D.E, D.k, none);\
+#define RR_LAUNCH_STREAM(NJ)                                                                                            \
+  do {                                                                                                                  \
+    constexpr int smem = RxLayout<BF16, NJ>::SMEM;                                                                      \
+    if (R) router_lds_kernel<BF16, NJ, true><<<grid, block, smem, s>>>(x, w_router, bias, logits, probs, rank_expert,    \
+                                                                       D.T, D.d, D.E, D.k, *R);                         \
+    else router_lds_kernel<BF16, NJ, false><<<grid, block, smem, s>>>(x, w_router, bias, logits, probs, rank_expert,     \
+                                                                      D.T, D.d, D.E, D.k, none);                        \
   } while (0)
-  const int NJ = D.E <= 32 ? 1 : 2;
-  const bool exact = D.d % (4 * KC) == 0 && D.E == NJ * 32;
-  if (NJ == 1 && exact) RR_LAUNCH_STREAM(1, true);
-  else if (NJ == 1) RR_LAUNCH_STREAM(1, false);
-  else if (exact) RR_LAUNCH_STREAM(2, true);
-  else RR_LAUNCH_STREAM(2, false);
+  if (D.E <= 32) RR_LAUNCH_STREAM(1);
+  else RR_LAUNCH_STREAM(2);
 #undef RR_LAUNCH_STREAM
 }
 
 }  // namespace
+
+// The streaming kernel's dynamic LDS exceeds the default limit: raised once per device by the caller.
+hipError_t router_kernel_attributes() {
+  hipError_t e = hipSuccess;
+  auto set = [&e](auto kern, int bytes) {
+    if (e == hipSuccess)
+      e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  };
+  set(router_lds_kernel<true, 1, true>, RxLayout<true, 1>::SMEM);
+  set(router_lds_kernel<true, 1, false>, RxLayout<true, 1>::SMEM);
+  set(router_lds_kernel<true, 2, true>, RxLayout<true, 2>::SMEM);
+  set(router_lds_kernel<true, 2, false>, RxLayout<true, 2>::SMEM);
+  set(router_lds_kernel<false, 1, true>, RxLayout<false, 1>::SMEM);
+  set(router_lds_kernel<false, 1, false>, RxLayout<false, 1>::SMEM);
+  set(router_lds_kernel<false, 2, true>, RxLayout<false, 2>::SMEM);
+  set(router_lds_kernel<false, 2, false>, RxLayout<false, 2>::SMEM);
+  return e;
+}
 
 static bool router_small(const Dims &D) { return D.T <= 64 * 1024; }
 int router_count_blocks(const Dims &D) { return router_small(D) ? kTokBlock / (router_tm(D) * 32) : 1; }
