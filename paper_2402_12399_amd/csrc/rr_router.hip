@@ -360,7 +360,8 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
 //     registers hold x in flight, so the ring is as deep as LDS allows;
 //   * a wave's part of the ring is its own, filled and read by nobody else: x needs no barrier,
 //     the wave waits (counted, vmcnt) for its own loads.  Ring of XS stages of one K chunk (128
-//     bytes of every row); chunk c + XS - 1 is requested while chunk c is multiplied.  Rows past
+//     bytes of every row); a chunk's fragments are read into registers first thing and chunk c + XS
+//     is requested into the stage that this frees, so XS chunks are in flight.  Rows past
 //     the batch and pieces past d_model lie outside the buffer range and read as zero; requests
 //     past the last chunk re-read the last chunk, so every chunk issues the same x loads and the
 //     counted wait holds for any shape;
@@ -383,7 +384,7 @@ struct RxLayout {
   static constexpr int ROWS = NJ * 32;               // expert rows staged
   static constexpr int ROWB = KC * 2;                // bytes of a staged bf16 weight row
   static constexpr int PART = ROWS * ROWB;           // one bf16 part of a weight chunk
-  static constexpr int WSTAGE = 3 * PART;
+  static constexpr int WSTAGE = 2 * PART;            // two bf16 parts of w
   static constexpr int XSTAGE = RX_TB * 128;         // one chunk of x for the workgroup: 16 KB
   static constexpr int XS = 3;                       // ring depth
   static constexpr int TSTR = ROWS + 1;
@@ -464,18 +465,17 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
     for (int q = 0; q < WLD; ++q) {
       const int idx = tid + q * RT_THREADS, e = idx / (KC / 4), f4 = idx % (KC / 4);
       const float keep = (e < E && kc + f4 * 4 < d) ? 1.0f : 0.0f;  // d_model % 8 == 0: four elements are in or out together
-      u32 h0, l0, m0, h1, l1, m1;
-      split3_pair(wreg[q].x * keep, wreg[q].y * keep, h0, l0, m0);
-      split3_pair(wreg[q].z * keep, wreg[q].w * keep, h1, l1, m1);
+      u32 h0, l0, h1, l1;
+      split2_pair(wreg[q].x * keep, wreg[q].y * keep, h0, l0);
+      split2_pair(wreg[q].z * keep, wreg[q].w * keep, h1, l1);
       const int off = e * ROWB + (((f4 >> 1) ^ wswz(e)) << 4) + (f4 & 1) * 8;
       // ds_write_b64 spelled out: the compiler makes an LDS store wait for every LDS-DMA load in flight
       // (it cannot tell the weight stages from the ring), which would drain the ring once per chunk
       typedef u32 u32x2 __attribute__((ext_vector_type(2)));
       const u32 a = (u32)(size_t)(__attribute__((address_space(3))) char *)(st + off);
-      const u32x2 ph = {h0, h1}, pl = {l0, l1}, pm = {m0, m1};
+      const u32x2 ph = {h0, h1}, pl = {l0, l1};
       asm volatile("ds_write_b64 %0, %1" ::"v"(a), "v"(ph) : "memory");
       asm volatile("ds_write_b64 %0, %1 offset:%2" ::"v"(a), "v"(pl), "n"(PART) : "memory");
-      asm volatile("ds_write_b64 %0, %1 offset:%2" ::"v"(a), "v"(pm), "n"(2 * PART) : "memory");
     }
   };
 
@@ -491,13 +491,12 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
   auto chunk = [&](int c, float4 (&wn)[WLD], float4 (&wo)[WLD]) {
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
     load_w(min(c + 2, nchunk - 1) * KC, wo);
-    issue_x(min(c + XS - 1, nchunk - 1), (c + XS - 1) % XS);
     __builtin_amdgcn_sched_barrier(0);
-    // x of chunk c was requested XS - 1 chunks ago and (XS - 1) NX x requests have been issued since:
-    // when no more loads than that are outstanding, it has landed (loads complete in order).  The
-    // weight loads are left out of the count on purpose - the compiler may move them across this
-    // wait in either direction, and counting a load that is not there would let the wait pass early;
-    // not counting one that is there only makes it wait for part of the next chunk's x as well.
+    // x of chunk c was requested XS chunks ago and (XS - 1) NX x requests have been issued since: when
+    // no more loads than that are outstanding, it has landed (loads complete in order).  The weight
+    // loads are left out of the count on purpose - the compiler may move them across this wait in
+    // either direction, and counting a load that is not there would let the wait pass early; not
+    // counting one that is there only makes it wait for part of the next chunk's x as well.
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"((XS - 1) * NX) : "memory");
     const char *sw = wst + (c & 1) * WSTAGE;
     // x fragments of the whole chunk, four 16-byte pieces per lane.  Read with ds_read_b128 spelled out:
@@ -511,18 +510,20 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
     asm volatile("ds_read_b128 %0, %1" : "=v"(xq2) : "v"(sx + (((4 * fh + 2) ^ fsw_x) << 4)) : "memory");
     asm volatile("ds_read_b128 %0, %1" : "=v"(xq3) : "v"(sx + (((4 * fh + 3) ^ fsw_x) << 4)) : "memory");
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xq0), "+v"(xq1), "+v"(xq2), "+v"(xq3)::"memory");
+    // the chunk is in registers and its stage free: chunk c + XS goes there, XS chunks are in flight
+    issue_x(min(c + XS, nchunk - 1), c % XS);
+    __builtin_amdgcn_sched_barrier(0);
     const uint4 xq[4] = {make_uint4(xq0.x, xq0.y, xq0.z, xq0.w), make_uint4(xq1.x, xq1.y, xq1.z, xq1.w),
                          make_uint4(xq2.x, xq2.y, xq2.z, xq2.w), make_uint4(xq3.x, xq3.y, xq3.z, xq3.w)};
 #pragma unroll
     for (int m = 0; m < KS; ++m) {
       const int posw = ((KS * fh + m) ^ fsw_w) << 4;
-      Frag wh[NJ], wl[NJ], wl2[NJ];
+      Frag wh[NJ], wl[NJ];
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         const char *rowp = sw + (j * 32 + fr) * ROWB + posw;
         wh[j].v = *reinterpret_cast<const bf16x8 *>(rowp);
         wl[j].v = *reinterpret_cast<const bf16x8 *>(rowp + PART);
-        wl2[j].v = *reinterpret_cast<const bf16x8 *>(rowp + 2 * PART);
       }
       if (BF16) {
         // lane (row fr, half fh) takes elements [32 fh + 8 m, +8): piece 4 fh + m
@@ -530,7 +531,6 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
         xf.w[0] = xq[m].x; xf.w[1] = xq[m].y; xf.w[2] = xq[m].z; xf.w[3] = xq[m].w;
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
-          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wl2[j].v, acc[j], 0, 0, 0);
           acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wl[j].v, acc[j], 0, 0, 0);
           acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xf.v, wh[j].v, acc[j], 0, 0, 0);
         }
@@ -539,21 +539,20 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
         Frag xh, xl;
         split2x8(xq[2 * m], xq[2 * m + 1], xh, xl);
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[j] = mfma5(xh, xl, wh[j], wl[j], wl2[j], acc[j]);
+        for (int j = 0; j < NJ; ++j) {  // the three products above 2^-18 of the leading one, smallest first
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xl.v, wh[j].v, acc[j], 0, 0, 0);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wl[j].v, acc[j], 0, 0, 0);
+          acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xh.v, wh[j].v, acc[j], 0, 0, 0);
+        }
       }
     }
     __builtin_amdgcn_sched_barrier(0);
     store_w((c + 1) & 1, min(c + 1, nchunk - 1) * KC, wn);
   };
-  static_assert(XS == 3, "the prologue requests two chunks");
   load_w(0, wbuf0);
-  __builtin_amdgcn_sched_barrier(0);
-  issue_x(0, 0);
-  __builtin_amdgcn_sched_barrier(0);
   load_w(min(1, nchunk - 1) * KC, wbuf1);
-  __builtin_amdgcn_sched_barrier(0);
-  issue_x(min(1, nchunk - 1), 1);
-  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int q = 0; q < XS; ++q) issue_x(min(q, nchunk - 1), q);
   store_w(0, 0, wbuf0);
   for (int c = 0; c < nchunk; c += 2) {  // two chunks per trip: the weight registers alternate without copies
     chunk(c, wbuf1, wbuf0);
