@@ -386,11 +386,12 @@ struct RxLayout {
   static constexpr int PART = ROWS * ROWB;           // one bf16 part of a weight chunk
   static constexpr int WSTAGE = 2 * PART;            // two bf16 parts of w
   static constexpr int XSTAGE = RX_TB * 128;         // one chunk of x for the workgroup: 16 KB
-  static constexpr int XS = 3;                       // ring depth
+  static constexpr int XS = 4;                       // ring depth: two pairs of chunks
   static constexpr int TSTR = ROWS + 1;
   static constexpr int TILE_BYTES = RT_NW * 32 * TSTR * 4;  // epilogue tiles reuse the ring
   static constexpr int X_BYTES = XS * XSTAGE > TILE_BYTES ? XS * XSTAGE : TILE_BYTES;
-  static constexpr int SMEM = X_BYTES + 2 * WSTAGE;
+  static constexpr int EPI_BYTES = (kMaxRounds * kMaxE + 2 * RT_NW * 32) * 4;  // epilogue counters and row statistics reuse the weight stages
+  static constexpr int SMEM = X_BYTES + (2 * WSTAGE > EPI_BYTES ? 2 * WSTAGE : EPI_BYTES);
 };
 
 template <bool BF16, int NJ, bool FUSE>
@@ -410,9 +411,11 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
   constexpr int NX = 32 * 128 / 1024;                // LDS-DMA instructions per wave per chunk (4)
   constexpr int KS = KC / 16;                        // MFMA k-steps per chunk
   extern __shared__ __attribute__((aligned(16))) char lds[];
-  __shared__ int cnt[kMaxRounds * kMaxE];
-  __shared__ float row_max[RT_NW][32], row_inv[RT_NW][32];
   char *const wst = lds + L::X_BYTES;
+  // only used after the K loop, in place of the weight stages (no static LDS: two workgroups fill a CU's 160 KB)
+  int *const cnt = reinterpret_cast<int *>(wst);
+  float(*const row_max)[32] = reinterpret_cast<float(*)[32]>(wst + kMaxRounds * kMaxE * 4);
+  float(*const row_inv)[32] = row_max + RT_NW;
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int fr = lane & 31, fh = lane >> 5;
@@ -420,6 +423,12 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
   const int fsw_w = wswz(fr), fsw_x = (fr >> 1) & 7;
   const int t0 = blockIdx.x * RX_TB, tw0 = t0 + w * 32;
   const int nchunk = (d + KC - 1) / KC;
+  // Workgroup b walks the K chunks from chunk 11 b mod nchunk on, wrapping around (the same order for x
+  // and w; a dot product does not care, only the rounding order of the sum changes with the block).
+  // Workgroups that run side by side would otherwise all ask for the same 128-byte column of their
+  // 4 KB rows at the same time, and those addresses fall on few memory channels (+6 % at 1M x 1024).
+  const int rot = (int)((blockIdx.x * 11u) % (unsigned)nchunk);
+  auto rc = [&](int c) { int q = c + rot; return q >= nchunk ? q - nchunk : q; };
 
   // ---- x: this wave's 32 rows as a buffer (rows past the batch are outside its range)
   const int rows_valid = max(0, min(32, T - tw0));
@@ -435,15 +444,19 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
     xpiece[i] = (lane & 7) ^ ((row >> 1) & 7);
     xoff[i] = row * d * ES + xpiece[i] * 16;
   }
-  auto issue_x = [&](int c, int stage) {
-    char *st = lds + stage * XSTAGE + w * (32 * 128);
-    const int koff = c * 128;  // byte offset of chunk c in a row
-    const bool tail = (c + 1) * KC > d;  // the last chunk of a d_model that is not a multiple of KC
+  // requests chunk ca into stage sa and chunk cb into stage sb, alternating between the two instruction by instruction
+  auto issue_x = [&](int ca, int sa, int cb, int sb) {
 #pragma unroll
     for (int i = 0; i < NX; ++i) {
-      auto lp = (__attribute__((address_space(3))) void *)(st + i * 1024);
-      const bool past = tail && c * KC + xpiece[i] * (16 / ES) >= d;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsx, lp, 16, past ? 0x7ffffff0 : xoff[i], koff, 0, 0);
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int c = h ? cb : ca, stage = h ? sb : sa;
+        auto lp = (__attribute__((address_space(3))) void *)(lds + stage * XSTAGE + w * (32 * 128) + i * 1024);
+        // pieces past d_model (the last chunk of a d_model that is not a multiple of KC) lie outside the range
+        const int cr = rc(c);
+        const bool past = (cr + 1) * KC > d && cr * KC + xpiece[i] * (16 / ES) >= d;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsx, lp, 16, past ? 0x7ffffff0 : xoff[i], cr * 128, 0, 0);
+      }
     }
   };
 
@@ -485,36 +498,21 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.0f;
 
-  // one K chunk.  On entry: the weights of chunk c + 1 are in `wn` (registers); this chunk's weights are
-  // in LDS stage c & 1 once the barrier has passed; x of chunks c .. c + XS - 2 has been requested.
-  // Every chunk issues WLD weight loads and NX x loads.
-  auto chunk = [&](int c, float4 (&wn)[WLD], float4 (&wo)[WLD]) {
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    load_w(min(c + 2, nchunk - 1) * KC, wo);
-    __builtin_amdgcn_sched_barrier(0);
-    // x of chunk c was requested XS chunks ago and (XS - 1) NX x requests have been issued since: when
-    // no more loads than that are outstanding, it has landed (loads complete in order).  The weight
-    // loads are left out of the count on purpose - the compiler may move them across this wait in
-    // either direction, and counting a load that is not there would let the wait pass early; not
-    // counting one that is there only makes it wait for part of the next chunk's x as well.
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((XS - 1) * NX) : "memory");
-    const char *sw = wst + (c & 1) * WSTAGE;
-    // x fragments of the whole chunk, four 16-byte pieces per lane.  Read with ds_read_b128 spelled out:
-    // the compiler makes an LDS read that follows an LDS-DMA load wait for that very load, i.e. for
-    // the ring's youngest request.  LDS operations return in order; the wait below covers these reads.
+  // x fragments of one chunk: four 16-byte pieces per lane.  Read with ds_read_b128 spelled out (see above).
+  typedef u32 u32x4 __attribute__((ext_vector_type(4)));
+  struct XFrag { u32x4 q0, q1, q2, q3; };
+  auto read_x = [&](int c, XFrag &f) {
     const u32 sx = (u32)(size_t)(__attribute__((address_space(3))) char *)(lds + (c % XS) * XSTAGE + w * (32 * 128) + fr * 128);
-    typedef u32 u32x4 __attribute__((ext_vector_type(4)));
-    u32x4 xq0, xq1, xq2, xq3;
-    asm volatile("ds_read_b128 %0, %1" : "=v"(xq0) : "v"(sx + (((4 * fh + 0) ^ fsw_x) << 4)) : "memory");
-    asm volatile("ds_read_b128 %0, %1" : "=v"(xq1) : "v"(sx + (((4 * fh + 1) ^ fsw_x) << 4)) : "memory");
-    asm volatile("ds_read_b128 %0, %1" : "=v"(xq2) : "v"(sx + (((4 * fh + 2) ^ fsw_x) << 4)) : "memory");
-    asm volatile("ds_read_b128 %0, %1" : "=v"(xq3) : "v"(sx + (((4 * fh + 3) ^ fsw_x) << 4)) : "memory");
-    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xq0), "+v"(xq1), "+v"(xq2), "+v"(xq3)::"memory");
-    // the chunk is in registers and its stage free: chunk c + XS goes there, XS chunks are in flight
-    issue_x(min(c + XS, nchunk - 1), c % XS);
-    __builtin_amdgcn_sched_barrier(0);
-    const uint4 xq[4] = {make_uint4(xq0.x, xq0.y, xq0.z, xq0.w), make_uint4(xq1.x, xq1.y, xq1.z, xq1.w),
-                         make_uint4(xq2.x, xq2.y, xq2.z, xq2.w), make_uint4(xq3.x, xq3.y, xq3.z, xq3.w)};
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f.q0) : "v"(sx + (((4 * fh + 0) ^ fsw_x) << 4)) : "memory");
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f.q1) : "v"(sx + (((4 * fh + 1) ^ fsw_x) << 4)) : "memory");
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f.q2) : "v"(sx + (((4 * fh + 2) ^ fsw_x) << 4)) : "memory");
+    asm volatile("ds_read_b128 %0, %1" : "=v"(f.q3) : "v"(sx + (((4 * fh + 3) ^ fsw_x) << 4)) : "memory");
+  };
+  // the arithmetic of one chunk: x fragments in registers, weights in LDS stage c & 1
+  auto multiply = [&](int c, const XFrag &f) {
+    const uint4 xq[4] = {make_uint4(f.q0.x, f.q0.y, f.q0.z, f.q0.w), make_uint4(f.q1.x, f.q1.y, f.q1.z, f.q1.w),
+                         make_uint4(f.q2.x, f.q2.y, f.q2.z, f.q2.w), make_uint4(f.q3.x, f.q3.y, f.q3.z, f.q3.w)};
+    const char *sw = wst + (c & 1) * WSTAGE;
 #pragma unroll
     for (int m = 0; m < KS; ++m) {
       const int posw = ((KS * fh + m) ^ fsw_w) << 4;
@@ -546,17 +544,48 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
         }
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
-    store_w((c + 1) & 1, min(c + 1, nchunk - 1) * KC, wn);
   };
-  load_w(0, wbuf0);
-  load_w(min(1, nchunk - 1) * KC, wbuf1);
+  // Two K chunks per trip.  x is requested in PAIRS of chunks, instruction by instruction, so that the
+  // two adjacent 128-byte lines of a row reach the memory together (one open DRAM page serves both).
+  // At the top of a trip the pair (c, c + 1) has landed: both chunks' fragments go into registers,
+  // which frees their stages for the pair (c + XS, c + XS + 1); two pairs are always in flight.
+  // The weights keep their own rhythm: chunk c's are in LDS stage c & 1 after the barrier, chunk
+  // c + 1's in registers (wbuf1), chunk c + 2's are fetched into wbuf0 meanwhile.
+  load_w(rc(0) * KC, wbuf0);
+  load_w(rc(min(1, nchunk - 1)) * KC, wbuf1);
 #pragma unroll
-  for (int q = 0; q < XS; ++q) issue_x(min(q, nchunk - 1), q);
-  store_w(0, 0, wbuf0);
-  for (int c = 0; c < nchunk; c += 2) {  // two chunks per trip: the weight registers alternate without copies
-    chunk(c, wbuf1, wbuf0);
-    if (c + 1 < nchunk) chunk(c + 1, wbuf0, wbuf1);
+  for (int q = 0; q < XS; q += 2) {
+    issue_x(min(q, nchunk - 1), q, min(q + 1, nchunk - 1), q + 1);
+  }
+  store_w(0, rc(0) * KC, wbuf0);
+  for (int c = 0; c < nchunk; c += 2) {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    load_w(rc(min(c + 2, nchunk - 1)) * KC, wbuf0);
+    __builtin_amdgcn_sched_barrier(0);
+    // The pair (c, c + 1) was requested XS chunks ago and one pair (2 NX x requests) has been issued since:
+    // when no more loads than that are outstanding, it has landed (loads complete in order).  The weight
+    // loads are left out of the count on purpose - the compiler may move them across this wait in either
+    // direction, and counting a load that is not there would let the wait pass early; not counting one
+    // that is there only makes it wait for part of the next pair as well.
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((XS - 2) * NX) : "memory");
+    XFrag f0, f1;
+    read_x(c, f0);
+    read_x(c + 1, f1);
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(f0.q0), "+v"(f0.q1), "+v"(f0.q2), "+v"(f0.q3), "+v"(f1.q0), "+v"(f1.q1), "+v"(f1.q2), "+v"(f1.q3)::"memory");
+    issue_x(min(c + XS, nchunk - 1), c % XS, min(c + XS + 1, nchunk - 1), (c + 1) % XS);
+    __builtin_amdgcn_sched_barrier(0);
+    multiply(c, f0);
+    __builtin_amdgcn_sched_barrier(0);
+    store_w((c + 1) & 1, rc(min(c + 1, nchunk - 1)) * KC, wbuf1);
+    if (c + 1 < nchunk) {
+      asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+      load_w(rc(min(c + 3, nchunk - 1)) * KC, wbuf1);
+      __builtin_amdgcn_sched_barrier(0);
+      multiply(c + 1, f1);
+      __builtin_amdgcn_sched_barrier(0);
+      store_w(c & 1, rc(min(c + 2, nchunk - 1)) * KC, wbuf0);
+    }
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // requests past the last chunk have landed: the ring becomes the tiles
   __syncthreads();
