@@ -176,6 +176,7 @@ static size_t carve(const Dims &D, bool forward, void *ws, Work *W) {
     W->tables.ir_offset = cv.take<int32_t>(E + 1);
     W->tables.ir_token = cv.take<int32_t>(T);
     W->tables.combine_w = cv.take<float>(T * (D.k + 2));
+    W->row_dest = cv.take<int32_t>(D.Rmax);
     W->x_disp = cv.take<char>((size_t)D.Rmax * D.d * es);
     W->h = cv.take<char>((size_t)D.Rmax * D.F * es);
     W->y = cv.take<char>((size_t)D.Rmax * D.d * es);
@@ -268,7 +269,7 @@ int rr_rectified_dispatch_static(const rr_config *cfg, const float *logits, cons
   Work W;
   memset(&W, 0, sizeof(W));
   carve(D, false, g_scratch_ptr[dev], &W);
-  hipError_t e = launch_dispatch(D, logits, *out, W, false, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_dispatch(D, logits, *out, W, false, nullptr, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
 }
 
@@ -283,7 +284,7 @@ int rr_rectified_dispatch(const rr_config *cfg, const float *logits, const rr_ta
   memset(&W, 0, sizeof(W));
   rc = check_ws(D, false, workspace, workspace_bytes, &W);
   if (rc != RR_OK) return rc;
-  hipError_t e = launch_dispatch(D, logits, *out, W, false, static_cast<hipStream_t>(stream));
+  hipError_t e = launch_dispatch(D, logits, *out, W, false, nullptr, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
 }
 
@@ -316,10 +317,11 @@ int rr_moe_forward(const rr_config *cfg, const void *x, const float *w_router, c
   D.cb = router_count_blocks(D);  // the router ranks and counts: per 32 tokens for small batches
   D.NBc = (D.T + kTokBlock / D.cb - 1) / (kTokBlock / D.cb);
   hipError_t e = launch_router(D, x, w_router, bias, lg, nullptr, nullptr, &tb, &W, s);
-  if (e == hipSuccess) e = launch_dispatch(D, lg, tb, W, true, s);
+  const bool direct = !routing_only && ffn_writes_single_rows(D);
+  if (e == hipSuccess) e = launch_dispatch(D, lg, tb, W, true, direct ? W.row_dest : nullptr, s);
   if (routing_only) return e == hipSuccess ? RR_OK : RR_ERR_HIP;
   if (e == hipSuccess && !ffn_fuses_gather(D)) e = launch_gather(D, x, tb, W, s);
-  if (e == hipSuccess) e = launch_ffn(D, x, tb, w1, w3, w2, W, s);
+  if (e == hipSuccess) e = launch_ffn(D, x, tb, w1, w3, w2, W, out, s);
   if (e == hipSuccess) e = launch_combine(D, tb, W, out, s);
   return e == hipSuccess ? RR_OK : RR_ERR_HIP;
 }

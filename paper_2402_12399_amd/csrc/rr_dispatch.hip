@@ -928,7 +928,8 @@ __global__ __launch_bounds__(kTokBlock) void ir_count_kernel(DispatchArgs A, con
 // also stores them with row_base and cuts every expert's rows into tiles of BM rows (skipped when
 // max_mtiles == 0: routing-only calls have no grouped GEMM).
 __device__ inline void row_plan_wave(const DispatchArgs &A, bool writes, const int32_t *__restrict__ fill_total,
-                                     const int32_t *__restrict__ ir_cnt, int *s_off, int32_t *__restrict__ ir_offset,
+                                     const int32_t *__restrict__ ir_cnt, int *s_off, int *s_rbase,
+                                     int32_t *__restrict__ ir_offset,
                                      int32_t *__restrict__ row_base, TileInfo *__restrict__ tiles,
                                      int32_t *__restrict__ tile_ctl) {
   const int e = threadIdx.x & 63;
@@ -943,7 +944,10 @@ __device__ inline void row_plan_wave(const DispatchArgs &A, bool writes, const i
     int a = __shfl_up(s_ir, off), b = __shfl_up(s_rows, off), c = __shfl_up(s_tiles, off);
     if (e >= off) { s_ir += a; s_rows += b; s_tiles += c; }
   }
-  if (on) s_off[e] = s_ir - nir;
+  if (on) {
+    s_off[e] = s_ir - nir;
+    s_rbase[e] = s_rows - rows;
+  }
   if (!writes) return;
   if (on) {
     ir_offset[e] = s_ir - nir;
@@ -993,10 +997,13 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
                                                                int32_t *__restrict__ ir_expert,
                                                                int32_t *__restrict__ ir_row,
                                                                int32_t *__restrict__ ir_token,
-                                                               float *__restrict__ combine_w) {
+                                                               float *__restrict__ combine_w,
+                                                               const int32_t *__restrict__ rank_expert,
+                                                               const int32_t *__restrict__ grp_off,
+                                                               int32_t *__restrict__ row_dest) {
   constexpr int NW = kTokBlock / kWave;
   __shared__ int wcnt[NW][kMaxE];
-  __shared__ int s_off[kMaxE];
+  __shared__ int s_off[kMaxE], s_rbase[kMaxE];
   const int tid = threadIdx.x, b = xcd_block(blockIdx.x, A.NB), w = tid >> 6;
   const int i = b * kTokBlock + tid;
   const bool valid = i < A.T;
@@ -1021,6 +1028,12 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
   if (valid && A.ir) {
     cand = ir_cand[i];
     score_h = ir_score[i];
+  }
+  int e_r[kMaxRank];  // only for row_dest: the experts behind the token's slots
+#pragma unroll
+  for (int r = 0; r < kMaxRank; ++r) {
+    e_r[r] = 0;
+    if (row_dest && valid && r < A.NR) e_r[r] = rank_expert[(size_t)i * (A.k + 1) + r];
   }
 #pragma unroll
   for (int r = 0; r < kMaxRank; ++r)
@@ -1047,10 +1060,11 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
   // the row plan is a few dozen numbers: every workgroup recomputes the list offsets it needs, the
   // first one also writes the plan out for the kernels that follow
   if (w == 0)
-    row_plan_wave(A, blockIdx.x == 0, fill_total, self ? s_cnt : ir_cnt, s_off, ir_offset, row_base, tiles, tile_ctl);
+    row_plan_wave(A, blockIdx.x == 0, fill_total, self ? s_cnt : ir_cnt, s_off, s_rbase, ir_offset, row_base, tiles, tile_ctl);
   __syncthreads();
   if (!valid) return;
   float a_h = 0.0f;
+  int my_ir_row = -1;
   if (has_ir) {
     int row = (A.ir_self ? s_before[h] : ir_blk_off[(size_t)h * A.NB + b]) + below;
     for (int q = 0; q < w; ++q) row += wcnt[q][h];
@@ -1058,9 +1072,27 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
     ir_row[i] = row;
     ir_token[s_off[h] + row] = i;
     a_h = score_h;
+    my_ir_row = row;
   } else {
     ir_expert[i] = -1;
     ir_row[i] = -1;
+  }
+  if (row_dest) {
+    // Every dispatched row belongs to one (token, assignment): the token marks each of its rows - with
+    // its own index if this is the token's only row (Eq. 2 / Eq. 3 then give it weight exactly 1 and the
+    // expert's output row IS the layer's output row: the down projection stores it there), else with -1.
+    int nrows = has_ir ? 1 : 0;
+#pragma unroll
+    for (int r = 0; r < kMaxRank; ++r) nrows += (r < A.NR && slot_r[r] >= 0) ? 1 : 0;
+    const int mark = nrows == 1 ? i : -1;
+#pragma unroll
+    for (int r = 0; r < kMaxRank; ++r) {
+      if (r < A.NR && slot_r[r] >= 0) {
+        const int e = e_r[r], g = slot_r[r] / A.Cq;
+        row_dest[s_rbase[e] + grp_off[e * A.Gq + g] + (slot_r[r] - g * A.Cq)] = mark;
+      }
+    }
+    if (has_ir) row_dest[s_rbase[h] + fill_total[h] + my_ir_row] = mark;
   }
   // Eq. 2 / Eq. 3: softmax over the successfully routed experts, a placed Fill-in expert, and the
   // Intra-GPU expert counted (k - |R_i|) times
@@ -1096,7 +1128,7 @@ __global__ __launch_bounds__(kTokBlock) void ir_weights_kernel(DispatchArgs A, c
 }  // namespace
 
 hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, bool ranked,
-                           hipStream_t s) {
+                           int32_t *row_dest, hipStream_t s) {
   DispatchArgs A{D.T, D.E, D.k, D.C, D.NR, D.NCAT, D.NB, D.Eg, D.Tg, D.ir, D.fr, D.arrival, D.BM, D.max_mtiles,
                  D.Cq, D.Gq, D.NL, D.NBc, D.cb, D.E * D.NB <= kIrSelfMax ? 1 : 0,
                  D.Gq == 1 && D.T <= kDirectMaxT ? 1 : 0};
@@ -1141,7 +1173,8 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
   prof_begin(K_IR_WEIGHTS, s);
   ir_weights_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.slot, W.key, W.ir_score, W.ir_cand, W.ir_blk_cnt, W.ir_cnt,
                                                tb.fill_total, tb.ir_offset, W.row_base, W.tiles, W.tile_ctl,
-                                               tb.ir_expert, tb.ir_row, tb.ir_token, tb.combine_w);
+                                               tb.ir_expert, tb.ir_row, tb.ir_token, tb.combine_w, tb.rank_expert,
+                                               W.grp_off, row_dest);
   prof_end(K_IR_WEIGHTS, s);
   if (D.quota && D.max_mtiles > 0)  // the forward pass addresses dispatched rows through row_token
     row_token_kernel<<<D.E, 256, 0, s>>>(A, tb.slot_token, W.grp_fill, W.grp_off, tb.fill_total, tb.ir_offset,

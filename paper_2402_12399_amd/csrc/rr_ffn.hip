@@ -95,6 +95,10 @@ struct GemmArgs {
   const int32_t *row_token;  // token of every dispatched row (per-group quotas), or NULL: rows are slots, then the Intra-GPU list
   int C;
   long long a_bytes;    // size of the A operand in bytes (buffer range of the gather)
+  // DIRECT only (down projection): row_dest[row] = the token whose only processed row this is, else -1;
+  // such a row is also stored as row row_dest[row] of Out, the layer's output (Eq. 2 with a single term)
+  const int32_t *row_dest;
+  void *Out;
 };
 
 // Epilogue shared by the bf16 kernels: activation, round to bf16, store (masked on edge tiles).
@@ -131,9 +135,10 @@ __device__ inline void store_tile(f32x16 (&acc)[WM][WN], uint16_t *Cb, int rbase
 // of the A fragment) and, per fragment, four groups of four consecutive columns
 // (8 * (v / 4) + 4 * (lane / 32) + v % 4): four 8-byte stores per fragment instead of sixteen
 // 2-byte ones.
-template <int WM, int WN, bool GATED, int ACT>
+// dest (DIRECT): per fragment row of this lane, the row of Ob that the same values are also stored to, or -1.
+template <int WM, int WN, bool GATED, int ACT, bool DIRECT = false>
 __device__ inline void store_tile_t(f32x16 (&acc)[WM][WN], uint16_t *Cb, int rbase, int rows_e, int m0, int n0, int N,
-                                    int wm, int wn, int lane) {
+                                    int wm, int wn, int lane, const int *dest = nullptr, uint16_t *Ob = nullptr) {
   constexpr int NJ = GATED ? WN / 2 : WN;  // output column fragments per wave
   const int fr = lane & 31, fh = lane >> 5;
   const int wrow0 = m0 + wm * WM * 32, wcol0 = n0 + wn * NJ * 32;
@@ -143,6 +148,8 @@ __device__ inline void store_tile_t(f32x16 (&acc)[WM][WN], uint16_t *Cb, int rba
     const int row = wrow0 + i * 32 + fr;
     if (row >= rows_e) continue;
     uint16_t *prow = Cb + (size_t)(rbase + row) * N + wcol0 + 4 * fh;
+    uint16_t *orow = nullptr;
+    if (DIRECT && dest[i] >= 0) orow = Ob + (size_t)dest[i] * N + wcol0 + 4 * fh;
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
 #pragma unroll
@@ -154,8 +161,11 @@ __device__ inline void store_tile_t(f32x16 (&acc)[WM][WN], uint16_t *Cb, int rba
           if (GATED) c[u] = silu_fast(c[u]) * acc[i][j + NJ][4 * g + u];
           if (ACT == RR_ACT_GELU) c[u] = gelu_erf(c[u]);
         }
-        if (cols_in || wcol0 + j * 32 + 8 * g + 4 * fh < N)
-          *reinterpret_cast<uint2 *>(prow + j * 32 + 8 * g) = make_uint2(pack_bf16(c[0], c[1]), pack_bf16(c[2], c[3]));
+        if (cols_in || wcol0 + j * 32 + 8 * g + 4 * fh < N) {
+          const uint2 val = make_uint2(pack_bf16(c[0], c[1]), pack_bf16(c[2], c[3]));
+          *reinterpret_cast<uint2 *>(prow + j * 32 + 8 * g) = val;
+          if (DIRECT && orow) *reinterpret_cast<uint2 *>(orow + j * 32 + 8 * g) = val;
+        }
       }
     }
   }
@@ -188,7 +198,7 @@ constexpr int PK_SMEM = PK_B_BASE + PK_B_STAGES * PK_B_STAGE;  // 160 KB: all of
 [[maybe_unused]] constexpr int PK_NI = (PK_BM + PK_BROWS) / 8 / PK_NW;  // 1 KB load instructions per wave per chunk
 [[maybe_unused]] constexpr int PK_NIA = PK_BM / 8 / PK_NW;
 
-template <bool GATED, int ACT, bool GATHER>
+template <bool GATED, int ACT, bool GATHER, bool DIRECT = false>
 __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmArgs P) {
 #if defined(__HIP_DEVICE_COMPILE__)  // buffer-resource and LDS-DMA builtins exist in the device pass only
   constexpr int WM = PK_WM, WN = PK_WN, NW = PK_NW, BM = PK_BM, NI = PK_NI, NIA = PK_NIA;
@@ -415,6 +425,15 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
     // than anything a counted wait lets pass
     if (GATHER) lookup_tokens(info1, tok1);
     raw_load(L2 >= 0 ? L2 : L, ra2, rb2);
+    int dest[WM];  // DIRECT: where the rows that this lane will store also go (this tile's, used in its epilogue)
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+      dest[i] = -1;
+      if (DIRECT) {
+        const int row = cur.m0 + (wm * WM + i) * 32 + fr;
+        dest[i] = P.row_dest[cur.rbase + min(row, cur.rows_e - 1)];
+      }
+    }
     __builtin_amdgcn_sched_barrier(0);
     issue_a(cur, 1, sa ^ 1);
     issue_b(cur, 2, next_b(next_b(sb)));
@@ -472,6 +491,10 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
       // and store.  Without a next tile the values are unused.
       make_tile(info1, tok1, nxt);
       info2 = finalize(L2 >= 0 ? L2 : L, ra2, rb2);
+      if (DIRECT) {  // consumed here like the other lookups, so that no load is pending when the loop is entered
+#pragma unroll
+        for (int i = 0; i < WM; ++i) asm volatile("" : "+v"(dest[i]));
+      }
       for (int kt = 1; kt < KT; ++kt) {
         // A(kt) and B(kt) have landed - the B issued after A(kt) may still be on its way - and
         // nobody reads the stages of chunk kt-1 any more
@@ -513,8 +536,8 @@ __global__ __launch_bounds__(PK_THREADS) void gemm_bf16_persistent_kernel(GemmAr
     if (have1) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NIB) : "memory");
     sa ^= 1;
     sb = next_b(sb);
-    store_tile_t<WM, WN, GATED, ACT>(acc, static_cast<uint16_t *>(P.Cout), cur.rbase, cur.rows_e, cur.m0, cur.n0, N, wm,
-                                     wn, lane);
+    store_tile_t<WM, WN, GATED, ACT, DIRECT>(acc, static_cast<uint16_t *>(P.Cout), cur.rbase, cur.rows_e, cur.m0, cur.n0,
+                                             N, wm, wn, lane, dest, static_cast<uint16_t *>(P.Out));
     if (!have1) break;
     cur = nxt;
     L = L1;
@@ -747,11 +770,14 @@ hipError_t ffn_kernel_attributes() {
   set(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, true>, PK_SMEM);
   set(gemm_bf16_persistent_kernel<false, RR_ACT_GELU, false>, PK_SMEM);
   set(gemm_bf16_persistent_kernel<false, -1, false>, PK_SMEM);
+  set(gemm_bf16_persistent_kernel<false, -1, false, true>, PK_SMEM);
   set(gemm_bf16_staged_kernel<true, -1>, PK_LDS);
   set(gemm_bf16_staged_kernel<false, RR_ACT_GELU>, PK_LDS);
   set(gemm_bf16_staged_kernel<false, -1>, PK_LDS);
   return e;
 }
+
+bool ffn_writes_single_rows(const Dims &D) { return D.dtype == RR_BF16 && persistent_ok(D.F); }
 
 bool ffn_fuses_gather(const Dims &D) {
   return D.dtype == RR_BF16 && persistent_ok(D.d) && (long long)D.T * D.d * 2 < 0x7ffffff0ll;
@@ -759,11 +785,11 @@ bool ffn_fuses_gather(const Dims &D) {
 
 // which: bit 0 = up projection (+ activation), bit 1 = down projection
 hipError_t launch_ffn_part(const Dims &D, const void *x, const rr_tables &tb, const void *w1, const void *w3,
-                           const void *w2, const Work &W, hipStream_t s, int which) {
+                           const void *w2, const Work &W, void *out, hipStream_t s, int which) {
   const bool fuse = ffn_fuses_gather(D);
   GemmArgs up{fuse ? x : W.x_disp, w1, w3, W.h, D.d, D.F, 0, W.tiles, W.tile_ctl,
-              tb.slot_token, tb.ir_token, D.quota ? W.row_token : nullptr, D.C, (long long)D.T * D.d * 2};
-  GemmArgs down{W.h, w2, nullptr, W.y, D.F, D.d, 0, W.tiles, W.tile_ctl, nullptr, nullptr, nullptr, 0, 0};
+              tb.slot_token, tb.ir_token, D.quota ? W.row_token : nullptr, D.C, (long long)D.T * D.d * 2, nullptr, nullptr};
+  GemmArgs down{W.h, w2, nullptr, W.y, D.F, D.d, 0, W.tiles, W.tile_ctl, nullptr, nullptr, nullptr, 0, 0, W.row_dest, out};
   if (D.dtype == RR_BF16) {
     const bool gated = D.act == RR_ACT_SWIGLU;
     up.NT = gated ? (D.F + 127) / 128 : (D.F + 255) / 256;
@@ -784,7 +810,7 @@ hipError_t launch_ffn_part(const Dims &D, const void *x, const rr_tables &tb, co
     }
     if (which & 2) {
       prof_begin(K_FFN_DOWN, s);
-      if (persistent_ok(D.F)) gemm_bf16_persistent_kernel<false, -1, false><<<cus, PK_THREADS, PK_SMEM, s>>>(down);
+      if (persistent_ok(D.F)) gemm_bf16_persistent_kernel<false, -1, false, true><<<cus, PK_THREADS, PK_SMEM, s>>>(down);
       else gemm_bf16_staged_kernel<false, -1><<<down.NT * D.max_mtiles, GS_THREADS, PK_LDS, s>>>(down);
       prof_end(K_FFN_DOWN, s);
     }
@@ -809,8 +835,8 @@ hipError_t launch_ffn_part(const Dims &D, const void *x, const rr_tables &tb, co
 }
 
 hipError_t launch_ffn(const Dims &D, const void *x, const rr_tables &tb, const void *w1, const void *w3,
-                      const void *w2, const Work &W, hipStream_t s) {
-  return launch_ffn_part(D, x, tb, w1, w3, w2, W, s, 3);
+                      const void *w2, const Work &W, void *out, hipStream_t s) {
+  return launch_ffn_part(D, x, tb, w1, w3, w2, W, out, s, 3);
 }
 
 }  // namespace rr

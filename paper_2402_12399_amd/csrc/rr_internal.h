@@ -78,6 +78,7 @@ struct Work {
   // forward only
   float   *logits;       // [T,E] when the caller passes none
   rr_tables tables;      // storage when the caller passes none
+  int32_t *row_dest;     // [Rmax] token whose ONLY processed row this is (its output row is written by the down projection), else -1
   void    *x_disp;       // [Rmax, d]
   void    *h;            // [Rmax, F]
   void    *y;            // [Rmax, d]
@@ -116,14 +117,16 @@ int router_count_blocks(const Dims &D);
 hipError_t launch_router(const Dims &D, const void *x, const float *w_router, const float *bias,
                          float *logits, float *probs, int32_t *rank_expert, const rr_tables *tb, const Work *W,
                          hipStream_t s);
+// row_dest: only in the forward call (see Work::row_dest), else nullptr
 hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &tb, const Work &W, bool ranked,
-                           hipStream_t s);
+                           int32_t *row_dest, hipStream_t s);
 hipError_t launch_gather(const Dims &D, const void *x, const rr_tables &tb, const Work &W, hipStream_t s);
 hipError_t router_kernel_attributes();  // raises the dynamic-LDS limit of the streaming router on the current device
 hipError_t ffn_kernel_attributes();     // raises the dynamic-LDS limit of the bf16 GEMM kernels on the current device
-bool ffn_fuses_gather(const Dims &D);  // the up projection reads x through the dispatch tables: no gather pass
+bool ffn_fuses_gather(const Dims &D);
+bool ffn_writes_single_rows(const Dims &D);  // the down projection writes the output row of a token with one processed assignment itself  // the up projection reads x through the dispatch tables: no gather pass
 hipError_t launch_ffn(const Dims &D, const void *x, const rr_tables &tb, const void *w1, const void *w3,
-                      const void *w2, const Work &W, hipStream_t s);
+                      const void *w2, const Work &W, void *out, hipStream_t s);
 hipError_t launch_combine(const Dims &D, const rr_tables &tb, const Work &W, void *out, hipStream_t s);
 // reads the expert outputs, row bases and block offsets that the forward pass left in W
 hipError_t launch_router_backward(const Dims &D, const void *dout, const float *logits, const rr_tables &tb,

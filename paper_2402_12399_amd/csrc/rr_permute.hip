@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4 *__restrict__ 
                                                       const int32_t *__restrict__ fill_total,
                                                       const int32_t *__restrict__ row_base,
                                                       const int32_t *__restrict__ grp_off, int Cq, int Gq,
-                                                      const float *__restrict__ combine_w) {
+                                                      const float *__restrict__ combine_w, int skip_single) {
   const int i = blockIdx.x;
   __shared__ int s_row[kMaxRank + 1];
   __shared__ float s_w[kMaxRank + 1];
@@ -118,6 +118,12 @@ __global__ __launch_bounds__(256) void combine_kernel(const uint4 *__restrict__ 
     s_w[r] = w;
   }
   __syncthreads();
+  if (skip_single) {  // a token with exactly one row: the down projection has stored its output row
+    int nrows = 0;
+#pragma unroll
+    for (int r = 0; r <= kMaxRank; ++r) nrows += s_row[r] >= 0;
+    if (nrows == 1) return;
+  }
   for (int v = threadIdx.x; v < vec_per_row; v += 256) {
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -153,7 +159,7 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(const uint4 *__restri
                                                            const int32_t *__restrict__ fill_total,
                                                            const int32_t *__restrict__ row_base,
                                                            const int32_t *__restrict__ grp_off, int Cq, int Gq,
-                                                           const float *__restrict__ combine_w) {
+                                                           const float *__restrict__ combine_w, int skip_single) {
   const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (i >= T) return;
   const int lane = lane_id();
@@ -173,6 +179,8 @@ __global__ __launch_bounds__(256) void combine_wave_kernel(const uint4 *__restri
       my_w = combine_w[(size_t)i * (k + 2) + k + 1];
     }
   }
+  // a token with exactly one row: the down projection has stored its output row
+  if (skip_single && __popcll(__ballot(my_row >= 0)) == 1) return;
   int row[kMaxRank + 1];
   float wgt[kMaxRank + 1];
 #pragma unroll
@@ -223,6 +231,7 @@ hipError_t launch_gather(const Dims &D, const void *x, const rr_tables &tb, cons
 hipError_t launch_combine(const Dims &D, const rr_tables &tb, const Work &W, void *out, hipStream_t s) {
   const int es = D.dtype == RR_BF16 ? 2 : 4;
   const int vec_per_row = D.d * es / 16;
+  const int skip = ffn_writes_single_rows(D) ? 1 : 0;
   prof_begin(K_COMBINE, s);
   // rows of up to 4 KB: one wave per token (no LDS, no barrier); longer rows: one workgroup per token
   if (vec_per_row <= 256) {
@@ -230,21 +239,21 @@ hipError_t launch_combine(const Dims &D, const rr_tables &tb, const Work &W, voi
       combine_wave_kernel<true><<<(D.T + 3) / 4, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out),
                                                               vec_per_row, D.T, D.k, D.NR, tb.rank_expert, tb.slot,
                                                               tb.ir_expert, tb.ir_row, tb.fill_total, W.row_base, W.grp_off,
-                                                              D.Cq, D.Gq, tb.combine_w);
+                                                              D.Cq, D.Gq, tb.combine_w, skip);
     else
       combine_wave_kernel<false><<<(D.T + 3) / 4, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out),
                                                                vec_per_row, D.T, D.k, D.NR, tb.rank_expert, tb.slot,
                                                                tb.ir_expert, tb.ir_row, tb.fill_total, W.row_base,
-                                                               W.grp_off, D.Cq, D.Gq, tb.combine_w);
+                                                               W.grp_off, D.Cq, D.Gq, tb.combine_w, skip);
   } else {
     if (D.dtype == RR_BF16)
       combine_kernel<true><<<D.T, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out), vec_per_row,
                                                D.k, D.NR, tb.rank_expert, tb.slot, tb.ir_expert, tb.ir_row,
-                                               tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w);
+                                               tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w, skip);
     else
       combine_kernel<false><<<D.T, 256, 0, s>>>(static_cast<const uint4 *>(W.y), static_cast<uint4 *>(out), vec_per_row,
                                                 D.k, D.NR, tb.rank_expert, tb.slot, tb.ir_expert, tb.ir_row,
-                                                tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w);
+                                                tb.fill_total, W.row_base, W.grp_off, D.Cq, D.Gq, tb.combine_w, skip);
   }
   prof_end(K_COMBINE, s);
   return hipGetLastError();
