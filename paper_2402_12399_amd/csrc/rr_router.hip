@@ -653,11 +653,6 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
 #endif
 }
 
-// Tokens per workgroup of the K-split kernel, in 32-token fragments: one for small batches, so that the
-// launch still fills the chip; two from 16 K tokens on (twice the reuse of every weight fragment), while
-// the partial tiles fit LDS (up to 32 experts).
-static int router_tm(const Dims &D) { return D.T > 16 * 1024 && D.E <= 32 ? 2 : 1; }
-
 template <bool BF16, int TM>
 void launch_one(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits, float *probs,
                 int32_t *rank_expert, const RankOut *R, hipStream_t s) {
@@ -710,8 +705,11 @@ hipError_t router_kernel_attributes() {
   return e;
 }
 
-static bool router_small(const Dims &D) { return D.T <= 64 * 1024; }
-int router_count_blocks(const Dims &D) { return router_small(D) ? kTokBlock / (router_tm(D) * 32) : 1; }
+// Up to 16 K tokens the K-split kernel (32 tokens per workgroup: 512 workgroups at 16 K tokens), above
+// the streaming kernel (128 tokens per workgroup; at 32 K tokens x 4096 bf16 it takes 76 us, the
+// K-split kernel 115 us; at 16 K tokens the K-split kernel is still ahead, 47 against 55 us).
+static bool router_small(const Dims &D) { return D.T <= 16 * 1024; }
+int router_count_blocks(const Dims &D) { return router_small(D) ? kTokBlock / 32 : 1; }
 
 hipError_t launch_router(const Dims &D, const void *x, const float *w_router, const float *bias, float *logits,
                          float *probs, int32_t *rank_expert, const rr_tables *tb, const Work *W, hipStream_t s) {
@@ -725,13 +723,8 @@ hipError_t launch_router(const Dims &D, const void *x, const float *w_router, co
                 D.k, D.NR, D.fr, D.Eg, D.Tg, D.NCAT, D.NBc};
   if (small) {
     const RankOut *Rp = tb && W ? &R : nullptr;
-    if (router_tm(D) == 2) {
-      if (D.dtype == RR_BF16) launch_one<true, 2>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
-      else launch_one<false, 2>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
-    } else {
-      if (D.dtype == RR_BF16) launch_one<true, 1>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
-      else launch_one<false, 1>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
-    }
+    if (D.dtype == RR_BF16) launch_one<true, 1>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
+    else launch_one<false, 1>(D, x, w_router, bias, logits, probs, rank_expert, Rp, s);
   } else {
     if (D.dtype == RR_BF16) launch_stream<true>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);
     else launch_stream<false>(D, x, w_router, bias, logits, probs, rank_expert, tb && W ? &R : nullptr, s);

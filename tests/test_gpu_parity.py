@@ -404,9 +404,9 @@ def test_c4_forward_routing_full_size():
 
 @pytest.mark.parametrize("dtype,d,E,k,G", [("f32", 256, 64, 2, 8), ("bf16", 512, 32, 1, 8), ("bf16", 256, 32, 2, 4)])
 def test_routing_only_forward_exact_path_real_inputs(dtype, d, E, k, G):
-    """Shapes that select the streaming router's unpredicated path (more than 64 K tokens; fp32 with
-    d_model % 128 == 0 and 64 experts, bf16 with d_model % 256 == 0 and 32 experts) with N(0,1) tokens
-    and N(0,0.02) router weights: logits against Eq. 1 in float64, tables from the library's own logits."""
+    """The streaming router (more than 16 K tokens) on whole-chunk shapes - fp32 with 64 experts, bf16
+    with 32 - with N(0,1) tokens and N(0,0.02) router weights: logits against Eq. 1 in float64, tables
+    from the library's own logits."""
     T = 66048 + 256 * G  # not a multiple of the router's 256-token workgroup
     T += 8 * G
     rng = np.random.default_rng(d + E)
@@ -452,7 +452,8 @@ def test_routing_only_forward_exact_path_dyadic(dtype, d, E, k, G):
 
 @pytest.mark.parametrize("dtype,E,k,G", [("f32", 64, 2, 8), ("bf16", 16, 1, 4), ("f32", 24, 4, 2)])
 def test_routing_only_forward_large_batch(dtype, E, k, G):
-    """Batches above 64K tokens take the streaming router whose epilogue also ranks (d_ff = 0: routing only).
+    """Large batches take the streaming router whose epilogue also ranks (d_ff = 0: routing only); here
+    d_model is not a whole number of K chunks and the expert counts do not fill the staged rows.
     Inputs are small dyadic rationals, so every dot product is exact in fp32 and in bf16 parts: the logits
     must equal the oracle's bit for bit, ties are frequent, and the tables must match exactly."""
     T, d = 66112 + 16 * G, 72
@@ -484,8 +485,9 @@ def test_routing_only_forward_large_batch(dtype, E, k, G):
 
 @pytest.mark.parametrize("dtype,E,k,G,quota", [("bf16", 32, 1, 8, False), ("f32", 16, 2, 4, True), ("bf16", 24, 3, 2, False)])
 def test_routing_only_forward_mid_batch(dtype, E, k, G, quota):
-    """Between 16 K and 64 K tokens and up to 32 experts the K-split router takes 64 tokens per workgroup
-    (candidate counts per 64 tokens).  Exact dyadic inputs: logits and tables must match bit for bit."""
+    """Just above 16 K tokens: the smallest batches of the streaming router (its grid does not fill the
+    chip), a ragged last workgroup, per-group capacity.  Exact dyadic inputs: logits and tables must
+    match bit for bit."""
     T, d = (20480 if quota else 20000 + 8 * G), 136
     rng = np.random.default_rng(3 * E + k)
     x = rng.integers(-3, 4, size=(T, d)).astype(np.float32) / np.float32(2.0)
