@@ -164,10 +164,16 @@ def run_forward(rr, wl, torch, w, mode, steps, warmup, quota=False, dev=None, ba
     d, F, T, E, k = w.d_model, w.d_ff, w.T, w.E, w.k
     flops = {"ffn_gate_up": (4 if gated else 2) * d * F * R, "ffn_down": 2 * d * F * R}
     # algorithmic HBM bytes per launch of the memory-bound kernels (each operand once)
-    n_src = int((th["slot"] >= 0).sum()) + ir_rows          # rows of y that combine reads
+    n_src = int((th["slot"] >= 0).sum()) + ir_rows          # processed assignments = rows of the expert outputs
+    rows_per_token = (th["slot"] >= 0).sum(axis=1) + (th["ir_expert"] >= 0)
+    # bf16 layers: the down projection stores the output row of a token with a single row itself, combine
+    # reads the rows of the other tokens and writes their output rows (and zero rows for unprocessed tokens)
+    direct = w.dtype == "bf16" and F % 64 == 0 and F >= 192
+    comb_read = int(rows_per_token[rows_per_token > 1].sum()) if direct else n_src
+    comb_write = int((rows_per_token != 1).sum()) if direct else T
     hbm = {"router_scores": T * d * es + T * E * 4 + E * d * 4,
            "dispatch_gather": 2 * R * d * es + 4 * R,
-           "combine": (n_src + T) * d * es + T * (k + 2) * 4}
+           "combine": (comb_read + comb_write) * d * es + T * (k + 2) * 4}
     hbm.update(dispatch_bytes(T, E, k, k + (1 if "fr" in mode else 0), C, ir_rows))
     if "topk_rank" not in kernels:  # the router's epilogue did the ranking: its table writes count for the router
         hbm["router_scores"] += hbm["topk_rank"] - 4 * T * E

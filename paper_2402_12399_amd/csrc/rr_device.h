@@ -41,4 +41,14 @@ __device__ inline void best_in_group(const float *row, int e0, int e1, float &be
 
 __device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }
 
+// Workgroup -> token block for kernels whose neighbouring token blocks write neighbouring words of
+// the same per-expert arrays.  Workgroups are dealt to the 8 XCDs round-robin and each XCD has its
+// own L2: with block = workgroup, one cache line would be completed piecewise from 8 L2s.  Here XCD
+// x walks its own contiguous eighth of the blocks, so the pieces of a line meet in one L2.
+__device__ inline int xcd_block(int g, int NB) {
+  const int per = NB >> 3, main = per << 3;
+  return g < main ? (g & 7) * per + (g >> 3) : g;
+}
+
+
 }  // namespace rr

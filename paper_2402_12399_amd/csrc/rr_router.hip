@@ -421,7 +421,10 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
   const int fr = lane & 31, fh = lane >> 5;
   auto wswz = [](int r) { return NCH == 8 ? ((r >> 1) & 7) : ((r >> 2) & 3); };
   const int fsw_w = wswz(fr), fsw_x = (fr >> 1) & 7;
-  const int t0 = blockIdx.x * RX_TB, tw0 = t0 + w * 32;
+  // token block of this workgroup: XCD-aware, because neighbouring blocks write neighbouring words of
+  // the per-list candidate counts (and neighbouring rows of every other output)
+  const int blk = xcd_block(blockIdx.x, gridDim.x);
+  const int t0 = blk * RX_TB, tw0 = t0 + w * 32;
   const int nchunk = (d + KC - 1) / KC;
   // Workgroup b walks the K chunks from chunk 11 b mod nchunk on, wrapping around (the same order for x
   // and w; a dot product does not care, only the rounding order of the sum changes with the block).
@@ -648,7 +651,7 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
   }
   if (FUSE) {
     __syncthreads();
-    for (int c = tid; c < R.NCAT; c += RT_THREADS) R.blk_cnt[(size_t)c * R.NBc + blockIdx.x] = cnt[c];
+    for (int c = tid; c < R.NCAT; c += RT_THREADS) R.blk_cnt[(size_t)c * R.NBc + blk] = cnt[c];
   }
 #endif
 }
