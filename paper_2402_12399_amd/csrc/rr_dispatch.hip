@@ -9,10 +9,12 @@
 //   topk_rank          per token: ranked experts, score keys, best expert of its own group,
 //                      candidate counts per (list, token block)
 //   scan_candidates    exclusive scan of those counts over token blocks, per list
-//   scatter_candidates stable split of the tokens into per-list arrays (ascending token index)
-//   select_slot        per list: kept count and first free slot from the counts, radix-select of
-//                      the score threshold of the kept set (ties -> lower token index), then a
-//                      prefix scan in token order hands out consecutive slots
+//   scatter_candidates stable split of the tokens into per-list arrays (ascending token index);
+//                      lists whose kept set follows from the counts (nobody, everybody, the first m
+//                      in token order) get their slots here and are not materialised
+//   select_slot        per remaining list: kept count and first free slot from the counts,
+//                      radix-select of the score threshold of the kept set (ties -> lower token
+//                      index), then a prefix scan in token order hands out consecutive slots
 //   ir_count / ir_scan / ir_weights
 //                      per-expert Intra-GPU lists (stable, token order), dispatched-row layout and
 //                      row tiles for the grouped GEMM, combine weights
@@ -175,6 +177,13 @@ __global__ __launch_bounds__(SC_THREADS) void scan_blocks_kernel(int32_t *__rest
 }
 
 // ------------------------------------------------------------------ scatter_candidates
+// Besides splitting the tokens into per-list arrays this kernel settles every list whose outcome
+// follows from the candidate counts alone: nobody kept (the capacity block is full), everybody kept,
+// or the first m in token order (arrival order).  A candidate's position in its list is known here,
+// so its slot is too: the token's slot entry is written with the rest of its row (whole cache
+// lines) and the candidate never enters the arrays.  Only the lists that are selected by score
+// (Sec. 3: the lowest scores are dropped; Sec. 4.2: Fill-in takes the highest) are materialised for
+// select_slot.
 __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchArgs A,
                                                                        const int32_t *__restrict__ rank_expert,
                                                                        const u32 *__restrict__ key,
@@ -182,10 +191,14 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
                                                                        const int32_t *__restrict__ cat_cnt,
                                                                        u32 *__restrict__ cand_key,
                                                                        int32_t *__restrict__ cand_tok,
-                                                                       int32_t *__restrict__ slot) {
+                                                                       int32_t *__restrict__ slot,
+                                                                       int32_t *__restrict__ slot_token) {
   constexpr int NW = kTokBlock / kWave;
   __shared__ int wcnt[kMaxRounds][NW][kMaxE];
   __shared__ int s_base[kMaxRounds * kMaxE];
+  // per list of this block's capacity block: first candidate (position in the candidate array), kept
+  // count (-1: selected by score, the list goes to select_slot) and first slot
+  __shared__ int s_lo[kMaxRounds * kMaxE], s_keep[kMaxRounds * kMaxE], s_fill0[kMaxRounds * kMaxE];
   const int tid = threadIdx.x, b = xcd_block(blockIdx.x, A.NB), w = tid >> 6, lane = tid & 63;
   const int i = b * kTokBlock + tid;
   const bool valid = i < A.T;
@@ -215,6 +228,27 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
     }
     if (lane < A.E) s_base[r * A.E + lane] = r * A.T + incl - c;
   }
+  // the plan of the lists that this block's tokens can be candidates of: capacity block g of every
+  // (round, expert); kept = min(candidates, free slots) round after round, as in select_slot
+  {
+    const int bpg = A.NB / A.Gq * A.cb, g = b / (A.NB / A.Gq);
+    for (int c = tid; c < A.NCAT; c += kTokBlock) {
+      const int r = c / A.E, j = c - r * A.E;
+      int n = 0, m = 0, fill = 0, lo = 0;
+      for (int rr = 0; rr <= r; ++rr) {
+        const int cc = rr * A.E + j;
+        fill += m;
+        lo = g == 0 ? 0 : blk_off[(size_t)cc * A.NBc + g * bpg];
+        const int hi = g == A.Gq - 1 ? cat_cnt[cc] : blk_off[(size_t)cc * A.NBc + (g + 1) * bpg];
+        n = hi - lo;
+        m = min(n, A.Cq - fill);
+      }
+      const bool by_score = !A.arrival || r == A.k;
+      s_lo[c] = lo;
+      s_keep[c] = (m == n || m == 0 || !by_score) ? m : -1;
+      s_fill0[c] = g * A.Cq + fill;
+    }
+  }
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < kMaxRounds; ++r) {
@@ -235,13 +269,18 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
   for (int r = 0; r < kMaxRounds; ++r) {
     if (r < A.NR) {
       int e = e_r[r], cat = r * A.E + e;
-      int pos = s_base[cat] + off_r[r] + rank_r[r];
-      for (int q = 0; q < w; ++q) pos += wcnt[r][q][e];
-      cand_key[pos] = key_r[r];
-      cand_tok[pos] = i;
-      // "dropped" until select_slot says otherwise: written here, token by token (whole cache lines),
-      // so that the list-major selection only has to touch the entries of the tokens it keeps
-      slot[(size_t)i * (A.k + 1) + r] = -1;
+      int at = off_r[r] + rank_r[r];  // position in the (round, expert) array
+      for (int q = 0; q < w; ++q) at += wcnt[r][q][e];
+      const int keep = s_keep[cat], idx = at - s_lo[cat];
+      int sl = -1;  // "dropped" until select_slot says otherwise (it only touches the entries of the tokens it keeps)
+      if (keep < 0) {
+        cand_key[s_base[cat] + at] = key_r[r];
+        cand_tok[s_base[cat] + at] = i;
+      } else if (idx < keep) {
+        sl = s_fill0[cat] + idx;
+        slot_token[(size_t)e * A.C + sl] = i;
+      }
+      slot[(size_t)i * (A.k + 1) + r] = sl;
     }
   }
 }
@@ -470,8 +509,8 @@ __device__ inline void select_streaming(const DispatchArgs &A, int n, int m, boo
 // longer list - a skewed router sends most tokens to a few experts - is cut into segments of
 // kSegLen candidates, one workgroup each (the first workgroups of the grid are the segments after a
 // list's first; each derives its (list, segment) from the candidate counts):
-//   * nobody, everybody or the first m in token order kept: a candidate's slot follows from its
-//     position alone, the segments need nothing from each other;
+//   * nobody, everybody or the first m in token order kept: scatter_candidates has handed out the
+//     slots already, the list's workgroups leave at once;
 //   * the m highest scores kept: every segment workgroup takes the same strided sample of the
 //     list's keys and selects in it a key L that, with a margin of several standard deviations,
 //     lies below the list's m-th highest key; it then copies its segment's candidates with key >= L,
@@ -622,18 +661,8 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
   }
   if (m == 0) return;  // nobody kept: every slot entry already says so
   const bool by_score = !A.arrival || r == A.k;  // the Fill-in round always selects by score (Sec. 4.2)
+  if (m == n || !by_score) return;  // everybody, or the first m in token order: settled by scatter_candidates
   const bool is_long = n > kRegMax;          // then, if can_split, the list has a workgroup per segment
-  if (m == n || !by_score) {
-    // everybody, or the first m in token order: slot = position
-    const bool cut = is_long && can_split;
-    const int i0 = cut ? seg * kSegLen : 0, i1 = min(m, cut ? i0 + kSegLen : n);
-    for (int idx = i0 + tid; idx < i1; idx += SS_THREADS) {
-      const int tok = toks[idx];
-      slot[(size_t)tok * (A.k + 1) + r] = fill0 + idx;
-      slot_token[(size_t)j * A.C + fill0 + idx] = tok;
-    }
-    return;
-  }
   if (!is_long) {
     select_in_registers(A, n, m, true, r, j, fill0, [&](int idx, u32 &kx, int &tok) { kx = keys[idx]; tok = toks[idx]; },
                         S, slot, slot_token);
@@ -1141,7 +1170,7 @@ hipError_t launch_dispatch(const Dims &D, const float *logits, const rr_tables &
     prof_end(K_SCAN_CAND, s);
     prof_begin(K_SCATTER_CAND, s);
     scatter_candidates_kernel<<<D.NB, kTokBlock, 0, s>>>(A, tb.rank_expert, W.key, W.blk_cnt, W.cat_cnt, W.cand_key,
-                                                         W.cand_tok, tb.slot);
+                                                         W.cand_tok, tb.slot, tb.slot_token);
     prof_end(K_SCATTER_CAND, s);
     prof_begin(K_SELECT_SLOT, s);
     // one workgroup per list, plus one for every further segment that a long list can have
