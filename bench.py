@@ -72,16 +72,39 @@ def parse():
     return ap.parse_args()
 
 
-def dispatch_bytes(T, E, k, NR, C, n_ir):
+def selected_candidates(rank_expert, E, NR, k, C, arrival=False):
+    """(candidates of the lists that are selected by score, kept candidates of the lists that the candidate
+    counts settle) for one queue of C slots per expert: a round keeps min(candidates, free slots); nobody,
+    everybody or (arrival policy, top-k rounds) the first ones in token order need no selection."""
+    n_sel = n_settled_kept = 0
+    fill = np.zeros(E, dtype=np.int64)
+    for r in range(NR):
+        n = np.bincount(rank_expert[:, r], minlength=E).astype(np.int64)
+        m = np.minimum(n, C - fill)
+        by_score = (not arrival) or r == k
+        sel = (m > 0) & (m < n) & by_score
+        n_sel += int(n[sel].sum())
+        n_settled_kept += int(m[~sel].sum())
+        fill += m
+    return n_sel, n_settled_kept
+
+
+def dispatch_bytes(T, E, k, NR, C, n_ir, n_sel=None, n_settled_kept=0):
     """Algorithmic HBM bytes per launch of the routing / rectification kernels: every table they read or
-    write, once, 4 bytes per entry (token blocks of 128 for the per-block candidate counts)."""
+    write, once, 4 bytes per entry (token blocks of 128 for the per-block candidate counts).  n_sel =
+    candidates that are materialised for select_slot (default: all of them)."""
     NB = (T + 127) // 128
     NCAT = NR * E
+    if n_sel is None:
+        n_sel = T * NR
     return {
         "topk_rank": 4 * (T * E + T * (k + 1) + T * NR + 2 * T + NCAT * NB),
         "scan_candidates": 4 * 2 * NCAT * NB,
-        "scatter_candidates": 4 * (2 * T * NR + NCAT * NB + 2 * T * NR),
-        "select_slot": 4 * (2 * T * NR + T * NR + E * C),
+        # ranks and keys in, block offsets in; the token's slot row out, (key, token) of a materialised
+        # candidate out, the token of a kept candidate of a settled list out
+        "scatter_candidates": 4 * (2 * T * NR + NCAT * NB + T * NR + 2 * n_sel + n_settled_kept),
+        # materialised candidates in; slot entries of the kept ones and the queues (kept + padding) out
+        "select_slot": 4 * (2 * n_sel + min(n_sel, E * C) + E * C - n_settled_kept),
         "ir_count": 4 * (T * (k + 1) + T + E * NB),
         "ir_scan": 4 * 2 * E * NB,
         "ir_weights": 4 * (T * (k + 1) + T * NR + 2 * T + E * NB + 2 * T + n_ir + T * (k + 2)),
@@ -174,7 +197,9 @@ def run_forward(rr, wl, torch, w, mode, steps, warmup, quota=False, dev=None, ba
     hbm = {"router_scores": T * d * es + T * E * 4 + E * d * 4,
            "dispatch_gather": 2 * R * d * es + 4 * R,
            "combine": (comb_read + comb_write) * d * es + T * (k + 2) * 4}
-    hbm.update(dispatch_bytes(T, E, k, k + (1 if "fr" in mode else 0), C, ir_rows))
+    NR = k + (1 if "fr" in mode else 0)
+    n_sel, n_settled = (None, 0) if (quota or T <= 16384) else selected_candidates(th["rank_expert"], E, NR, k, C)
+    hbm.update(dispatch_bytes(T, E, k, NR, C, ir_rows, n_sel, n_settled))
     if "topk_rank" not in kernels:  # the router's epilogue did the ranking: its table writes count for the router
         hbm["router_scores"] += hbm["topk_rank"] - 4 * T * E
     peak_tf = PEAK_BF16_TFLOPS if w.dtype == "bf16" else PEAK_FP32_TFLOPS
@@ -454,7 +479,8 @@ def routing_stress(rr, wl, torch, steps, warmup, cpu=False, zipf=None):
     n_ir = int(th["ir_offset"][-1])
     cand = np.bincount(th["rank_expert"][:, 0], minlength=w.E)
     NR = w.k + 1
-    hbm = dispatch_bytes(w.T, w.E, w.k, NR, tables.capacity, n_ir)
+    n_sel, n_settled = selected_candidates(th["rank_expert"], w.E, NR, w.k, tables.capacity)
+    hbm = dispatch_bytes(w.T, w.E, w.k, NR, tables.capacity, n_ir, n_sel, n_settled)
     router_bytes = w.T * w.d_model * 4 + w.T * w.E * 4 + w.E * w.d_model * 4 + hbm.pop("topk_rank") - 4 * w.T * w.E
     gbs = router_bytes / (kernels["router_scores"] * 1e-3) / 1e9
     disp = [n for n in kernels if n != "router_scores"]

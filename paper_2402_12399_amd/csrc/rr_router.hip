@@ -10,6 +10,8 @@
 //            ~1e-6 of a logit after the random-sign sum); x_hi.(w_hi + w_lo + w_lo2) + x_lo.(w_hi + w_lo)
 //            (5 MFMAs; a third x part would double the splitting arithmetic, which is what bounds
 //            the fp32 kernel, for accuracy below the fp32 rounding of the accumulation itself)
+// The streaming kernel for large batches keeps two parts of w (18 bits, the precision it keeps of
+// fp32 x anyway): x.w_hi + x.w_lo for bf16 x, x_hi.w_hi + x_hi.w_lo + x_lo.w_hi for fp32 x.
 // This keeps the kernel near the one pass over x in HBM instead of bound by fp32 FMA throughput.
 //
 // A workgroup of 4 waves owns TM*32 tokens; the waves split K four ways and each streams its K slice
@@ -356,7 +358,7 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
 //     row r at position c ^ ((r >> 1) & 7)).  Reading x with one row per lane, straight into the
 //     fragment registers, makes every wave instruction touch 64 different lines for 16 bytes each,
 //     and the rate at which the load unit looks lines up - not HBM - then bounds the kernel
-//     (measured: 4.1 TB/s of algorithmic bytes at 1M x 1024 fp32 tokens, against 4.3 here).  No
+//     (measured: 4.1 TB/s of algorithmic bytes at 1M x 1024 fp32 tokens, against 4.9 here).  No
 //     registers hold x in flight, so the ring is as deep as LDS allows;
 //   * a wave's part of the ring is its own, filled and read by nobody else: x needs no barrier,
 //     the wave waits (counted, vmcnt) for its own loads.  Ring of XS stages of one K chunk (128
@@ -365,11 +367,11 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
 //     the batch and pieces past d_model lie outside the buffer range and read as zero; requests
 //     past the last chunk re-read the last chunk, so every chunk issues the same x loads and the
 //     counted wait holds for any shape;
-//   * the router weights go through LDS as well: every K chunk of w is split into its three bf16
+//   * the router weights go through LDS as well: every K chunk of w is split into its two bf16
 //     parts ONCE per workgroup and stored as MFMA operand rows (swizzled like x); the weights of
 //     chunk c + 2 are fetched (global -> registers) during chunk c and written to LDS at the end
 //     of chunk c + 1; two stages, one barrier per chunk;
-//   * two workgroups per CU (each about 74 KB of LDS): one's epilogue overlaps the other's stream;
+//   * two workgroups per CU (each at most 80 KB of LDS): one's epilogue overlaps the other's stream;
 //   * the epilogue goes through a per-wave LDS tile; with a RankOut it also does the per-token work
 //     that the routing tables start from (see rank_row), so the logits are not read back from HBM.
 // What the compiler must not see: it makes every LDS load or store that follows an LDS-DMA load
