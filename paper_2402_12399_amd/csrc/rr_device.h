@@ -7,26 +7,36 @@ namespace rr {
 
 constexpr int kMaxRank = kMaxK + 1;
 
-// Eq. 1 argtopk over one row of scores held in LDS: the n best experts by descending score,
-// ties -> lower expert index (a later expert must be strictly greater to displace an earlier one).
-__device__ inline void top_n_of_row(const float *row, int E, int n, float (&bs)[kMaxRank], int (&be)[kMaxRank]) {
+// Ranking key of a (score, expert) pair: the order-preserving image of the score in the high word,
+// the complement of the expert index in the low one.  A greater key is a better rank - a higher
+// score, or an equal score at a lower expert index (Eq. 1 argtopk, ties -> lower expert index) - so
+// the order is ONE unsigned comparison, and the keys of different experts never tie.  0 lies below
+// every real key (the image of a score is never 0) and decodes to expert -1.
+__device__ inline unsigned long long rank_key(float v, int e) {
+  return ((unsigned long long)score_key(v) << 32) | (u32)~e;
+}
+__device__ inline int rank_key_expert(unsigned long long key) { return (int)~(u32)key; }
+__device__ inline u32 rank_key_score(unsigned long long key) { return (u32)(key >> 32); }
+
+// b[0] > b[1] > ... > b[N-1] are the N greatest keys seen so far: one compare-exchange per position.
+template <int N>
+__device__ inline void insert_key(unsigned long long (&b)[N], unsigned long long a) {
 #pragma unroll
-  for (int q = 0; q < kMaxRank; ++q) { bs[q] = -INFINITY; be[q] = -1; }
-  for (int e = 0; e < E; ++e) {
-    float cv = row[e];
-    int ce = e;
-    bool ins = false;
-#pragma unroll
-    for (int q = 0; q < kMaxRank; ++q) {
-      bool s = (q < n) && (ins || cv > bs[q]);
-      if (s) {
-        float tv = bs[q]; int te = be[q];
-        bs[q] = cv; be[q] = ce;
-        cv = tv; ce = te;
-        ins = true;
-      }
-    }
+  for (int q = 0; q < N; ++q) {
+    const bool c = a > b[q];
+    const unsigned long long hi = c ? a : b[q];
+    a = c ? b[q] : a;
+    b[q] = hi;
   }
+}
+
+// Eq. 1 argtopk over experts [e0, e1) of one row of scores held in LDS: the N best keys, best first
+// (positions past the number of experts stay 0).
+template <int N>
+__device__ inline void top_keys_of_range(const float *row, int e0, int e1, unsigned long long (&b)[N]) {
+#pragma unroll
+  for (int q = 0; q < N; ++q) b[q] = 0ull;
+  for (int e = e0; e < e1; ++e) insert_key(b, rank_key(row[e], e));
 }
 
 // Sec. 4.1: best expert among those of one group, ties -> lower expert index.

@@ -91,16 +91,16 @@ __global__ __launch_bounds__(kTokBlock) void topk_rank_kernel(const float *__res
   if (tid < ntok) {
     const int i = t0 + tid;
     const float *row = tile + tid * TS;
-    float bs[kMaxRank];
-    int be[kMaxRank];
     const int n = min(A.k + 1, E);
-    top_n_of_row(row, E, n, bs, be);
+    unsigned long long top[kMaxRank];
+    top_keys_of_range<kMaxRank>(row, 0, E, top);
 #pragma unroll
     for (int q = 0; q < kMaxRank; ++q) {
-      if (q <= A.k) rank_expert[(size_t)i * (A.k + 1) + q] = (q < n) ? be[q] : -1;
+      const int e = rank_key_expert(top[q]);  // -1 past the number of experts
+      if (q <= A.k) rank_expert[(size_t)i * (A.k + 1) + q] = (q < n) ? e : -1;
       if (q < A.NR) {
-        key[(size_t)i * A.NR + q] = score_key(bs[q]);
-        atomicAdd(&cnt[q * E + be[q]], 1);
+        key[(size_t)i * A.NR + q] = rank_key_score(top[q]);
+        atomicAdd(&cnt[q * E + e], 1);
       }
     }
     if (!A.fr) slot[(size_t)i * (A.k + 1) + A.k] = -1;

@@ -21,6 +21,8 @@
 // which K is fed to the MFMAs is permuted by that, identically for x and w, which a dot product does
 // not see.  The four partial tiles are summed through LDS in a fixed order (deterministic), then the
 // finished [token][expert] tile leaves as coalesced logits / probs rows and one lane per token ranks.
+#include <type_traits>
+
 #include "rr_device.h"
 
 namespace rr {
@@ -97,28 +99,47 @@ struct RankOut {
   int k, NR, fr, Eg, Tg, NCAT, NBc;
 };
 
-// One lane ranks one token from its finished row of logits (LDS): the top-(k+1) experts; with FUSE
-// also what the routing tables start from - score keys, the candidate counts of the token's count
-// block (LDS atomics on cnt[round * E + expert]), the best expert of the token's own group
-// (Sec. 4.1) - so that the logits are not read back from HBM.
+// Two lanes rank one token from its finished row of logits (LDS): lanes l and l + 32 of a wave
+// (half = 0, 1) each find the best experts of one half of the row, exchange them and merge, so the
+// serial scan is half as long; both lanes of a token must call this together.  Lane half 0 then
+// writes the top-(k+1) experts and, with FUSE, what the routing tables start from - score keys, the
+// candidate counts of the token's count block (LDS atomics on cnt[round * E + expert]) - and lane
+// half 1 the best expert of the token's own group (Sec. 4.1), so that the logits are not read back
+// from HBM.
 template <bool FUSE>
-__device__ inline void rank_row(const float *row, int tok, int E, int k, int32_t *rank_expert, const RankOut &R,
-                                int *cnt) {
-  float bs[kMaxRank];
-  int be[kMaxRank];
+__device__ inline void rank_row(const float *row, int tok, int half, int E, int k, int32_t *rank_expert,
+                                const RankOut &R, int *cnt) {
   const int n = min(k + 1, E);
-  top_n_of_row(row, E, n, bs, be);
+  const int h = (E + 1) >> 1;
   int32_t *ranks = FUSE ? R.rank_expert : rank_expert;
+  auto rank = [&](auto tag) {
+    constexpr int N = decltype(tag)::value;  // list length: at least n
+    unsigned long long b[N], o[N];
+    top_keys_of_range<N>(row, half ? h : 0, half ? E : h, b);
 #pragma unroll
-  for (int q = 0; q < kMaxRank; ++q) {
-    if (q <= k) ranks[(size_t)tok * (k + 1) + q] = (q < n) ? be[q] : -1;
-    if (FUSE && q < R.NR) {
-      R.key[(size_t)tok * R.NR + q] = score_key(bs[q]);
-      atomicAdd(&cnt[q * E + be[q]], 1);
+    for (int q = 0; q < N; ++q) {  // the other half's list (fetched whole before this lane's own list changes)
+      const u32 lo = __shfl_xor((u32)b[q], 32), hi = __shfl_xor((u32)(b[q] >> 32), 32);
+      o[q] = ((unsigned long long)hi << 32) | lo;
     }
-  }
-  if (FUSE) {
-    if (!R.fr) R.slot[(size_t)tok * (k + 1) + k] = -1;
+#pragma unroll
+    for (int q = 0; q < N; ++q) insert_key(b, o[q]);
+    if (half == 0) {
+#pragma unroll
+      for (int q = 0; q < kMaxRank; ++q) {
+        const unsigned long long key = q < N ? b[q < N ? q : 0] : 0ull;
+        const int e = rank_key_expert(key);  // -1 past the number of experts
+        if (q <= k) ranks[(size_t)tok * (k + 1) + q] = (q < n) ? e : -1;
+        if (FUSE && q < R.NR) {
+          R.key[(size_t)tok * R.NR + q] = rank_key_score(key);
+          atomicAdd(&cnt[q * E + e], 1);
+        }
+      }
+      if (FUSE && !R.fr) R.slot[(size_t)tok * (k + 1) + k] = -1;
+    }
+  };
+  if (n <= 3) rank(std::integral_constant<int, 3>{});
+  else rank(std::integral_constant<int, kMaxRank>{});
+  if (FUSE && half == 1) {
     const int g = tok / R.Tg;
     float best;
     int arg;
@@ -323,20 +344,20 @@ __global__ __launch_bounds__(RT_THREADS) void router_kernel(const void *__restri
     int row = idx / E, e = idx - row * E;
     logits[(size_t)t0 * E + idx] = tile[row * TS + e];
   }
-  if (tid < ntok) {
+  if (tid < ntok && probs) {
     const float *row = tile + tid * TS;
-    if (probs) {
-      float m = row[0];
-      for (int e = 1; e < E; ++e) m = fmaxf(m, row[e]);
-      float s = 0.0f;
-      for (int e = 0; e < E; ++e) s += expf(row[e] - m);
-      row_max[tid] = m;
-      row_inv[tid] = 1.0f / s;
-    }
-    // more than 16 experts: one lane per token (the E^2 comparisons of rank_tile then cost more
-    // than the serial insertion saves)
-    if ((rank_expert || FUSE) && E > 16) rank_row<FUSE>(row, t0 + tid, E, k, rank_expert, R, cnt);
+    float m = row[0];
+    for (int e = 1; e < E; ++e) m = fmaxf(m, row[e]);
+    float s = 0.0f;
+    for (int e = 0; e < E; ++e) s += expf(row[e] - m);
+    row_max[tid] = m;
+    row_inv[tid] = 1.0f / s;
   }
+  // more than 16 experts: two lanes per token, each scanning half the row (the E^2 comparisons of
+  // rank_tile then cost more than the serial insertion saves); lanes l and l + 32 of wave 0 share token l
+  static_assert(TB <= 32, "the two lanes of a token sit in one wave");
+  if ((rank_expert || FUSE) && E > 16 && tid < 64 && (tid & 31) < ntok)
+    rank_row<FUSE>(tile + (tid & 31) * TS, t0 + (tid & 31), tid >> 5, E, k, rank_expert, R, cnt);
   if ((rank_expert || FUSE) && E <= 16) rank_tile<FUSE>(tile, TS, ntok, t0, E, k, rank_expert, R, cnt);
   if (probs || FUSE) __syncthreads();
   if (probs) {
@@ -630,19 +651,17 @@ __global__ __launch_bounds__(RT_THREADS, 2) void router_lds_kernel(const void *_
         logits[(size_t)tf0 * E + idx] = tile[row * TSTR + e];
       }
     }
-    if (lane < ntok) {
+    if (lane < ntok && probs) {
       const float *row = tile + lane * TSTR;
-      const int tok = tf0 + lane;
-      if (probs) {
-        float mx = row[0];
-        for (int e = 1; e < E; ++e) mx = fmaxf(mx, row[e]);
-        float sum = 0.0f;
-        for (int e = 0; e < E; ++e) sum += expf(row[e] - mx);
-        row_max[w][lane] = mx;
-        row_inv[w][lane] = 1.0f / sum;
-      }
-      if (rank_expert || FUSE) rank_row<FUSE>(row, tok, E, k, rank_expert, R, cnt);
+      float mx = row[0];
+      for (int e = 1; e < E; ++e) mx = fmaxf(mx, row[e]);
+      float sum = 0.0f;
+      for (int e = 0; e < E; ++e) sum += expf(row[e] - mx);
+      row_max[w][lane] = mx;
+      row_inv[w][lane] = 1.0f / sum;
     }
+    // lanes l and l + 32 rank token l of the wave's 32 together
+    if ((rank_expert || FUSE) && fr < ntok) rank_row<FUSE>(tile + fr * TSTR, tf0 + fr, fh, E, k, rank_expert, R, cnt);
     if (probs) {
       __builtin_amdgcn_wave_barrier();
       for (int idx = lane; idx < ntok * E; idx += kWave) {
