@@ -301,12 +301,15 @@ constexpr int kHistWords = 256 * (1 + kHistCopies);
 // bin, and LDS atomics of one instruction on one address are served one lane after the other: every
 // bin has kHistCopies counters, lane l adds to copy l % kHistCopies (consecutive words, different
 // banks), and the copies are added up before the bins are scanned.
+// last_pass > 0 stops after the digits above it: the result is then the threshold with its lower digits
+// cleared - a lower bound of the m-th largest key that is off by less than one step of the last digit
+// taken (need_eq is meaningless then).
 template <class Each>
-__device__ inline u32 radix_select(int m, Each each, u32 *hist, u32 *s_pick, u32 &need_eq) {
+__device__ inline u32 radix_select(int m, Each each, u32 *hist, u32 *s_pick, u32 &need_eq, int last_pass = 0) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   u32 *copies = hist + 256;  // [256][kHistCopies]
   u32 prefix = 0, remaining = (u32)m;
-  for (int pass = 3; pass >= 0; --pass) {
+  for (int pass = 3; pass >= last_pass; --pass) {
     const int shift = pass * 8;
 #pragma unroll
     for (int q = 0; q < 256 * kHistCopies / SS_THREADS; ++q) copies[q * SS_THREADS + tid] = 0;
@@ -511,9 +514,9 @@ __device__ inline void select_streaming(const DispatchArgs &A, int n, int m, boo
 // list's first; each derives its (list, segment) from the candidate counts):
 //   * nobody, everybody or the first m in token order kept: scatter_candidates has handed out the
 //     slots already, the list's workgroups leave at once;
-//   * the m highest scores kept: every segment workgroup takes the same strided sample of the
-//     list's keys and selects in it a key L that, with a margin of several standard deviations,
-//     lies below the list's m-th highest key; it then copies its segment's candidates with key >= L,
+//   * the m highest scores kept: every segment workgroup takes the same sample of the list's keys
+//     (runs of 64 consecutive candidates, spread evenly) and selects in it a key L that, with a
+//     margin of several standard deviations, lies below the list's m-th highest key; it then copies its segment's candidates with key >= L,
 //     in order, to a second pair of arrays and counts them.  The workgroup that finishes last
 //     (a ticket from an atomic counter - nobody waits for anybody) adds up the counts: if they
 //     number at least m and fit the registers, the kept set is among them and it finishes the
@@ -682,15 +685,21 @@ __global__ __launch_bounds__(SS_THREADS) void select_slot_kernel(DispatchArgs A,
   }
   u32 L;
   {
-    const int stride = n / kSampleLen;  // >= 1: n > kRegMax > kSampleLen
+    // the sample: kSampleLen / 64 runs of 64 consecutive candidates, spread evenly over the list (a wave
+    // instruction then reads one run - two cache lines - where single candidates a stride apart would
+    // touch 64 lines: 19 -> 5 us for a list of 900 K candidates)
+    static_assert(kSegPer * SS_WAVES * kWave == kSampleLen, "one run per (trip, wave)");
+    const int run = n / (kSampleLen / kWave);  // > 64: n > kRegMax
     u32 sk[kSegPer];
 #pragma unroll
-    for (int u = 0; u < kSegPer; ++u) sk[u] = keys[(size_t)(u * SS_THREADS + tid) * stride];
+    for (int u = 0; u < kSegPer; ++u) sk[u] = keys[(size_t)(u * SS_WAVES + w) * run + lane];
     u32 dummy;
+    // the two leading digits are enough: L only has to lie below the list's m-th highest key, and the keys of
+    // one 16-bit step (2^-7 of a score) are a handful of candidates more
     L = radix_select(qsel, [&](auto f) {
 #pragma unroll
       for (int u = 0; u < kSegPer; ++u) f(sk[u], true);
-    }, S.hist, S.pick, dummy);
+    }, S.hist, S.pick, dummy, 2);
   }
   {
     const unsigned long long below = (1ull << lane) - 1ull;
