@@ -450,7 +450,8 @@ def test_routing_only_forward_exact_path_dyadic(dtype, d, E, k, G):
     gu.assert_tables_equal(tb.to_host(), orc.route(a, k, G, 0.75, True, True))
 
 
-@pytest.mark.parametrize("dtype,E,k,G", [("f32", 64, 2, 8), ("bf16", 16, 1, 4), ("f32", 24, 4, 2)])
+@pytest.mark.parametrize("dtype,E,k,G", [("f32", 64, 2, 8), ("bf16", 16, 1, 4), ("f32", 24, 4, 2), ("f32", 33, 2, 1),
+                                         ("bf16", 17, 1, 1)])
 def test_routing_only_forward_large_batch(dtype, E, k, G):
     """Large batches take the streaming router whose epilogue also ranks (d_ff = 0: routing only); here
     d_model is not a whole number of K chunks and the expert counts do not fill the staged rows.
