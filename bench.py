@@ -100,9 +100,9 @@ def dispatch_bytes(T, E, k, NR, C, n_ir, n_sel=None, n_settled_kept=0):
     return {
         "topk_rank": 4 * (T * E + T * (k + 1) + T * NR + 2 * T + NCAT * NB),
         "scan_candidates": 4 * 2 * NCAT * NB,
-        # ranks and keys in, block offsets in; the token's slot row out, (key, token) of a materialised
-        # candidate out, the token of a kept candidate of a settled list out
-        "scatter_candidates": 4 * (2 * T * NR + NCAT * NB + T * NR + 2 * n_sel + n_settled_kept),
+        # ranks in, the keys of materialised candidates in, block offsets in; the token's slot row out, (key, token)
+        # of a materialised candidate out, the token of a kept candidate of a settled list out
+        "scatter_candidates": 4 * (T * NR + n_sel + NCAT * NB + T * NR + 2 * n_sel + n_settled_kept),
         # materialised candidates in; slot entries of the kept ones and the queues (kept + padding) out
         "select_slot": 4 * (2 * n_sel + min(n_sel, E * C) + E * C - n_settled_kept),
         "ir_count": 4 * (T * (k + 1) + T + E * NB),

@@ -203,18 +203,14 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
   const int i = b * kTokBlock + tid;
   const bool valid = i < A.T;
   for (int c = tid; c < kMaxRounds * NW * kMaxE; c += kTokBlock) (&wcnt[0][0][0])[c] = 0;
-  // the token's own data is fetched in the same round trip as the array counts below (loads do not
+  // the token's experts are fetched in the same round trip as the array counts below (loads do not
   // move across barriers by themselves)
   int e_r[kMaxRounds], rank_r[kMaxRounds], off_r[kMaxRounds];
   u32 key_r[kMaxRounds];
 #pragma unroll
   for (int r = 0; r < kMaxRounds; ++r) {
     e_r[r] = 0;
-    key_r[r] = 0;
-    if (valid && r < A.NR) {
-      e_r[r] = rank_expert[(size_t)i * (A.k + 1) + r];
-      key_r[r] = key[(size_t)i * A.NR + r];
-    }
+    if (valid && r < A.NR) e_r[r] = rank_expert[(size_t)i * (A.k + 1) + r];
   }
   // every token is a candidate of exactly one array per round: round r's arrays tile [r T, (r+1) T)
   // in expert order (a dozen counts: recomputed by every workgroup rather than by a launch of its own)
@@ -254,9 +250,14 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
   for (int r = 0; r < kMaxRounds; ++r) {
     rank_r[r] = 0;
     off_r[r] = 0;
+    key_r[r] = 0;
     if (r < A.NR) {
       const int e = e_r[r];
-      if (valid) off_r[r] = blk_off[(size_t)(r * A.E + e) * A.NBc + b * A.cb];  // in flight across the barrier
+      // in flight across the barrier, and only what the list's plan needs: nothing for a list that keeps
+      // nobody, the position for a list that keeps by position, the key as well for a score-selected one
+      const int keep = s_keep[r * A.E + e];
+      if (valid && keep != 0) off_r[r] = blk_off[(size_t)(r * A.E + e) * A.NBc + b * A.cb];
+      if (valid && keep < 0) key_r[r] = key[(size_t)i * A.NR + r];
       unsigned long long mask = same_expert_mask(valid, e);
       int below = lanes_below(mask);
       if (valid && below == 0) wcnt[r][w][e] = __popcll(mask);
@@ -276,7 +277,7 @@ __global__ __launch_bounds__(kTokBlock) void scatter_candidates_kernel(DispatchA
       if (keep < 0) {
         cand_key[s_base[cat] + at] = key_r[r];
         cand_tok[s_base[cat] + at] = i;
-      } else if (idx < keep) {
+      } else if (keep > 0 && idx < keep) {  // (keep == 0: the position was not even fetched)
         sl = s_fill0[cat] + idx;
         slot_token[(size_t)e * A.C + sl] = i;
       }
