@@ -647,18 +647,22 @@ def test_dispatch_random_configurations():
 
 
 def test_routing_only_forward_random_configurations():
-    """The same through rr_moe_forward with d_ff = 0 (the router's fused ranking instead of topk_rank):
-    inputs are small dyadic rationals, so the logits are exact and the tables must match bit for bit."""
+    """The same through rr_moe_forward with d_ff = 0 (the router's fused ranking instead of topk_rank; every
+    fourth draw is a batch for the streaming router): inputs are small dyadic rationals, so the logits are
+    exact and the tables must match bit for bit."""
     rng = np.random.default_rng(77)
     done = 0
-    while done < 24:
-        G = int(rng.choice([1, 2, 4]))
+    while done < 32:
+        G = int(rng.choice([1, 2, 4, 8]))
         E = G * int(rng.integers(1, 64 // G + 1))
         k = int(rng.integers(1, 4))
         if k + 1 > E:
             continue
         quota = bool(rng.integers(0, 2))
-        T = G * 128 * int(rng.integers(1, 10)) if quota else G * int(rng.integers(10, 1200))
+        if done % 4 == 3:  # above 16 K tokens: the streaming router and materialised selection lists
+            T = G * 128 * int(rng.integers(130 // G + 1, 400 // G + 2)) if quota else G * int(rng.integers(16385 // G + 1, 70000 // G))
+        else:
+            T = G * 128 * int(rng.integers(1, 10)) if quota else G * int(rng.integers(10, 1200))
         d = 8 * int(rng.integers(2, 40))
         dtype = "bf16" if rng.integers(0, 2) else "f32"
         x = rng.integers(-3, 4, size=(T, d)).astype(np.float32) / np.float32(2.0)
